@@ -1,0 +1,219 @@
+/*
+ * graft.h - C ABI of the hybrid-tree verification hot path for MI355X (gfx950).
+ *
+ * One decoding round of prune-then-graft speculative decoding verifies a
+ * hybrid tree: retained draft nodes plus retrieved continuations appended
+ * into the slots pruning released (paper Sec. 3; App. A, Alg. 1 loop body and
+ * Alg. 2 last steps).  This library is the data-parallel part of that round:
+ *
+ *     graft_retrieve         ranked continuation chains to graft
+ *     graft_build_tree_mask  flattened parent list -> ancestor masks, positions, paths
+ *     graft_tree_attn        tree-masked GQA attention over a paged KV cache (per layer)
+ *     graft_accept           greedy acceptance walk
+ *
+ * Conventions shared by every call
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *    never allocates, frees or keeps them.  Scratch memory comes from
+ *    caller-provided workspaces whose sizes the *_workspace_bytes functions
+ *    (pure host functions) return.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *    only enqueue kernels: they never synchronize and never copy to the host.
+ *  - Return value: GRAFT_OK or a GRAFT_ERR_* code.  Arguments are validated on
+ *    the host before anything is launched; on error nothing is launched.
+ *  - Data-dependent faults (a length out of range, an ill-formed tree) cannot be
+ *    seen by the host.  They are reported per sequence in a caller-provided
+ *    int32 status[B] device array as GRAFT_STATUS_* bit flags, and the outputs of
+ *    that sequence are still fully defined (documented per call).
+ *  - Tree convention: node 0 is the root = the current token x_t (retrieval and
+ *    drafting are both rooted at it, Sec. 3.2), parent[0] = -1, and every other
+ *    node's parent has a smaller index (the flattened parent-child order of
+ *    Sec. 3.3).  Nodes >= n_nodes[b] are padding.  K_max <= GRAFT_MAX_NODES.
+ *  - Integers are int32_t, masks uint64_t, all arrays dense row-major with the
+ *    shapes given in brackets.
+ */
+#ifndef GRAFT_H
+#define GRAFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GRAFT_MAX_NODES   128   /* tree slots per sequence, root included          */
+#define GRAFT_MASK_WORDS  2     /* uint64 words per ancestor mask (bit j of word j/64) */
+#define GRAFT_MAX_CHAINS  8     /* C: chains returned per sequence                  */
+#define GRAFT_MAX_NGRAM   32    /* n_max: longest suffix matched                    */
+#define GRAFT_PAGE_SIZE   16    /* tokens per KV page                               */
+#define GRAFT_ARGMAX_CHUNKS 16  /* vocabulary chunks per logits row in graft_accept */
+
+/* return codes */
+#define GRAFT_OK             0
+#define GRAFT_ERR_NULL       1   /* a required pointer is NULL                       */
+#define GRAFT_ERR_SHAPE      2   /* a size or stride is outside the supported range  */
+#define GRAFT_ERR_DTYPE      3   /* unknown dtype enum                               */
+#define GRAFT_ERR_WORKSPACE  4   /* workspace NULL or smaller than *_workspace_bytes */
+#define GRAFT_ERR_HIP        5   /* a launch failed; see graft_last_hip_error()      */
+
+/* per-sequence status bit flags (device side) */
+#define GRAFT_STATUS_BAD_LENGTH     1  /* ctx_len / tail_len outside [0, L_max] / [0, tail_max] */
+#define GRAFT_STATUS_BAD_TREE       2  /* n_nodes outside [1, K_max], parent[0] != -1, or parent[i] not in [0, i) */
+#define GRAFT_STATUS_PATH_OVERFLOW  4  /* a path deeper than depth_cap or more leaves than n_leaf_max */
+
+/* element types of Q / K / V / O */
+#define GRAFT_F32   0
+#define GRAFT_BF16  1
+
+/* Raw hipError_t of the last failed launch on this thread (0 if none). */
+int32_t graft_last_hip_error(void);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t graft_version(void);
+
+/*
+ * graft_retrieve - suffix n-gram lookup over the whole context token buffer.
+ *
+ * This is the prompt-lookup / suffix-matching form of retrieval that the paper
+ * positions its method against (Sec. 3.2 first paragraph) and names as the
+ * online n-gram branch to add (Sec. 6 "Limitations and future work"); the
+ * chains it returns are what gets grafted into the released slots (Sec. 3.2
+ * "merge", App. A Alg. 2 "append K_ret retrieved nodes").
+ *
+ * For sequence b let L = ctx_len[b] and q = ctx[b,0..L) followed by
+ * tail[b,0..tail_len[b]) (the tokens on the tree path from below the root to
+ * the node the chains will hang from; tail may be NULL = empty).  A position
+ * e, 1 <= e <= L-1, is a hit when the longest l <= min(n_max, e) such that
+ * ctx[b,e-l..e) equals the last l tokens of q satisfies l >= n_min.  Hits are
+ * ranked by (l descending, e descending) - longest match first, most recent
+ * first - and for the best C of them the library returns
+ *     chain_pos   [B,C]    e                       (-1 if fewer than C hits)
+ *     chain_match [B,C]    l                       (0)
+ *     chain_len   [B,C]    min(m, L - e)           (0)
+ *     chain_tok   [B,C,m]  ctx[b,e..e+chain_len), then -1 padding (all -1)
+ *     n_hits      [B]      total number of hits
+ * The end of the buffer (e = L) is never a candidate and duplicate
+ * continuations are not merged.
+ *
+ * ctx [B,L_max], ctx_len [B], tail [B,tail_max] or NULL, tail_len [B] or NULL.
+ * Requires 1 <= n_min <= n_max <= GRAFT_MAX_NGRAM, 1 <= C <= GRAFT_MAX_CHAINS,
+ * m >= 1, B >= 1, L_max >= 1, L_max < 2^30.
+ * status[b] = GRAFT_STATUS_BAD_LENGTH if ctx_len[b] or tail_len[b] is out of
+ * range; that sequence then reports no hits.
+ */
+int32_t graft_retrieve(const int32_t* ctx, const int32_t* ctx_len, int32_t B, int32_t L_max,
+                       const int32_t* tail, const int32_t* tail_len, int32_t tail_max,
+                       int32_t n_min, int32_t n_max, int32_t C, int32_t m,
+                       int32_t* chain_tok, int32_t* chain_len, int32_t* chain_pos,
+                       int32_t* chain_match, int32_t* n_hits, int32_t* status, void* stream);
+
+/*
+ * graft_build_tree_mask - the "rebuild" step: from the flattened hybrid tree's
+ * parent list to "tree position IDs, ancestor mask, and candidate-path
+ * indices" (Sec. 3.3 "Hybrid-tree verification"; App. A Alg. 2, last step).
+ *
+ *     mask  [B,K_max,GRAFT_MASK_WORDS]  bit j set iff j == i or j is an ancestor of i
+ *     depth [B,K_max]                   edges from the root
+ *     pos   [B,K_max]                   prefix_len[b] + depth   (position id)
+ *     paths [B,n_leaf_max,depth_cap+1]  optional (NULL to skip): one row per leaf
+ *                                       in increasing leaf index, node indices
+ *                                       root..leaf, -1 padded; unused rows -1
+ * Padding nodes get mask 0, depth -1, pos -1.  A leaf deeper than depth_cap
+ * gets an all -1 row and leaves beyond n_leaf_max are dropped; both raise
+ * GRAFT_STATUS_PATH_OVERFLOW.  An ill-formed tree raises GRAFT_STATUS_BAD_TREE and
+ * gives mask 0 and -1 everywhere else for that sequence.
+ *
+ * parent [B,K_max], n_nodes [B], prefix_len [B].  1 <= K_max <= GRAFT_MAX_NODES;
+ * with paths: n_leaf_max >= 1, 0 <= depth_cap < GRAFT_MAX_NODES.
+ */
+int32_t graft_build_tree_mask(const int32_t* parent, const int32_t* n_nodes, const int32_t* prefix_len,
+                              int32_t B, int32_t K_max,
+                              uint64_t* mask, int32_t* pos, int32_t* depth,
+                              int32_t* paths, int32_t n_leaf_max, int32_t depth_cap,
+                              int32_t* status, void* stream);
+
+/*
+ * graft_tree_attn - the attention inside the single parallel verification
+ * pass over the hybrid tree (Sec. 3.3: the tree is sent to the target model
+ * "in one parallel verification pass" with the standard ancestor mask; long
+ * context runs use scaled dot-product attention, Sec. 3.3 "Long-context
+ * adaptation").  One call = one layer.
+ *
+ * For sequence b, node i < n_nodes[b], query head h (KV head g = h / (Hq/Hkv)):
+ *     S   = {prefix tokens 0..P-1} U {tree slot j : bit j of mask[b,i] set},  P = prefix_len[b]
+ *     out[b,i,h,:] = sum_{t in S} softmax_t( scale * q[b,i,h,:] . k_t[g,:] ) * v_t[g,:]
+ * i.e. causal attention of node i over the prefix and its own root-to-node
+ * path.  Tree slot j is logical token P + j of the sequence: the K/V of all
+ * tree tokens, the root's included, sit in the same paged cache right after
+ * the prefix.  Rows of padding nodes are written as zeros.  No rotary
+ * embedding is applied here: q and k arrive already position-encoded (the
+ * position ids come from graft_build_tree_mask).
+ *
+ * q, out     [B,K_max,Hq,D]   dtype elements
+ * k_cache, v_cache            paged; element d of KV head g of the token at
+ *                             in-page offset o of physical page p is at index
+ *                             p*page_stride + o*token_stride + g*head_stride + d
+ *                             (strides in elements; the D elements contiguous)
+ * block_table [B,max_pages]   physical page of each logical page; logical token
+ *                             t is in page block_table[b, t/page_size] at offset
+ *                             t % page_size.  (P + n_nodes[b]) <= max_pages*page_size
+ *                             is the caller's responsibility.
+ * prefix_len [B], n_nodes [B], mask [B,K_max,GRAFT_MASK_WORDS] (from graft_build_tree_mask)
+ * scale                       softmax scale, normally 1/sqrt(D)
+ * dtype                       GRAFT_F32: fp32 storage and arithmetic throughout.
+ *                             GRAFT_BF16: bf16 storage, fp32 scores/softmax/accumulation,
+ *                             probabilities rounded to bf16 for the P.V product.
+ * workspace                   at least graft_tree_attn_workspace_bytes(...) bytes,
+ *                             256-byte aligned; contents are scratch.
+ *
+ * Requires D in {64,128}, Hq % Hkv == 0, Hq/Hkv <= 16, page_size == GRAFT_PAGE_SIZE,
+ * 1 <= K_max <= GRAFT_MAX_NODES, max_pages >= 1, token_stride and head_stride
+ * multiples of 8 elements, all sizes positive.
+ */
+size_t graft_tree_attn_workspace_bytes(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int32_t D,
+                                       int32_t max_pages, int32_t dtype);
+
+int32_t graft_tree_attn(const void* q, const void* k_cache, const void* v_cache,
+                        int64_t page_stride, int64_t token_stride, int64_t head_stride,
+                        const int32_t* block_table, int32_t max_pages,
+                        const int32_t* prefix_len, const int32_t* n_nodes, const uint64_t* mask,
+                        int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int32_t D, int32_t page_size,
+                        float scale, int32_t dtype, void* out,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * graft_accept - the acceptance step under greedy decoding: the unchanged
+ * speculative rule (Sec. 3.3; App. A Alg. 1 "select the accepted path";
+ * App. B.4) specialised to the greedy setting of the main results (Sec. 4).
+ *
+ * t*[i] = the target's greedy token after node i.  Two modes:
+ *   logits == NULL : target_ids [B,K_max] is an INPUT holding t*.
+ *   logits != NULL : logits [B,K_max,V] fp32; t*[i] = index of the first maximum
+ *                    of row i (inputs assumed NaN-free) and target_ids is an
+ *                    OUTPUT receiving t* (-1 for padding nodes); needs workspace.
+ * The root is accepted; node i > 0 is accepted iff its parent is accepted and
+ * tokens[b,i] == t*[parent[i]].  best = accepted node of greatest depth not
+ * exceeding depth_cap (smallest index on ties).
+ *     accept_len [B]              depth of best (root and bonus token not counted)
+ *     best_node  [B]
+ *     path       [B,depth_cap+1]  node indices root..best, -1 padded
+ *     out_tokens [B,depth_cap+1]  tokens of path[1..], then the bonus token t*[best], -1 padded
+ * An accepted node deeper than depth_cap raises GRAFT_STATUS_PATH_OVERFLOW.  An
+ * ill-formed tree raises GRAFT_STATUS_BAD_TREE with accept_len 0, best_node -1,
+ * path/out_tokens (and target_ids in logits mode) all -1.
+ *
+ * parent, tokens [B,K_max], n_nodes [B].  0 <= depth_cap < GRAFT_MAX_NODES,
+ * logits mode: V >= 1, workspace >= graft_accept_workspace_bytes(B,K_max,V).
+ */
+size_t graft_accept_workspace_bytes(int32_t B, int32_t K_max, int32_t V);
+
+int32_t graft_accept(const int32_t* parent, const int32_t* tokens, const int32_t* n_nodes,
+                     const float* logits, int32_t V, int32_t* target_ids,
+                     int32_t B, int32_t K_max, int32_t depth_cap,
+                     int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* out_tokens,
+                     int32_t* status, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRAFT_H */

@@ -1,0 +1,150 @@
+"""Host-side checks of the C-ABI library (no GPU): it loads, exports every symbol that
+include/graft.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "graft.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_20104_amd as g
+    if not os.path.exists(g.LIB_PATH):
+        from paper_2605_20104_amd import build
+        build.build()
+    return g.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(graft_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    import paper_2605_20104_amd as g
+    names = declared_functions()
+    assert {"graft_retrieve", "graft_build_tree_mask", "graft_tree_attn", "graft_accept"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert sorted(g.EXPORTED_SYMBOLS) == names
+
+
+def test_header_constants_match_binding():
+    import paper_2605_20104_amd as g
+    text = open(HEADER).read()
+    for name in ("GRAFT_MAX_NODES", "GRAFT_MASK_WORDS", "GRAFT_MAX_CHAINS", "GRAFT_MAX_NGRAM",
+                 "GRAFT_PAGE_SIZE", "GRAFT_ERR_NULL", "GRAFT_ERR_SHAPE", "GRAFT_ERR_DTYPE",
+                 "GRAFT_ERR_WORKSPACE", "GRAFT_ERR_HIP", "GRAFT_STATUS_BAD_LENGTH", "GRAFT_STATUS_BAD_TREE",
+                 "GRAFT_STATUS_PATH_OVERFLOW", "GRAFT_F32", "GRAFT_BF16"):
+        m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
+        assert m and int(m.group(1)) == getattr(g, name), name
+
+
+def test_version_and_error_state(lib):
+    assert lib.graft_version() >= 100
+    assert lib.graft_last_hip_error() == 0
+
+
+P = 0x1000      # a non-NULL placeholder: validation must fail before any pointer is touched
+
+
+def test_retrieve_validation(lib):
+    import paper_2605_20104_amd as g
+    f = lib.graft_retrieve
+    ok = [P, P, 1, 64, None, None, 0, 2, 4, 2, 4, P, P, P, P, P, P, None]
+
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return f(*a)
+    assert call(a0=None) == g.GRAFT_ERR_NULL
+    assert call(a11=None) == g.GRAFT_ERR_NULL
+    assert call(a4=P) == g.GRAFT_ERR_NULL                 # tail without tail_len
+    assert call(a2=0) == g.GRAFT_ERR_SHAPE                # B
+    assert call(a3=0) == g.GRAFT_ERR_SHAPE                # L_max
+    assert call(a7=0) == g.GRAFT_ERR_SHAPE                # n_min < 1
+    assert call(a7=5) == g.GRAFT_ERR_SHAPE                # n_min > n_max
+    assert call(a8=g.GRAFT_MAX_NGRAM + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a9=g.GRAFT_MAX_CHAINS + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a9=0) == g.GRAFT_ERR_SHAPE
+    assert call(a10=0) == g.GRAFT_ERR_SHAPE
+
+
+def test_tree_mask_validation(lib):
+    import paper_2605_20104_amd as g
+    f = lib.graft_build_tree_mask
+    assert f(None, P, P, 1, 16, P, P, P, None, 0, 0, P, None) == g.GRAFT_ERR_NULL
+    assert f(P, P, P, 1, 16, P, P, P, None, 0, 0, None, None) == g.GRAFT_ERR_NULL
+    assert f(P, P, P, 0, 16, P, P, P, None, 0, 0, P, None) == g.GRAFT_ERR_SHAPE
+    assert f(P, P, P, 1, g.GRAFT_MAX_NODES + 1, P, P, P, None, 0, 0, P, None) == g.GRAFT_ERR_SHAPE
+    assert f(P, P, P, 1, 16, P, P, P, P, 0, 4, P, None) == g.GRAFT_ERR_SHAPE       # paths but no rows
+    assert f(P, P, P, 1, 16, P, P, P, P, 4, g.GRAFT_MAX_NODES, P, None) == g.GRAFT_ERR_SHAPE
+
+
+def test_tree_attn_validation_and_workspace(lib):
+    import paper_2605_20104_amd as g
+    f = lib.graft_tree_attn
+    ws = lib.graft_tree_attn_workspace_bytes
+    ok = [P, P, P, 8 * 16 * 128, 128, 16 * 128, P, 130, P, P, P, 1, 40, 32, 8, 128, 16,
+          0.088, g.GRAFT_BF16, P, P, 1 << 40, None]
+
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return f(*a)
+    assert call(a0=None) == g.GRAFT_ERR_NULL
+    assert call(a10=None) == g.GRAFT_ERR_NULL
+    assert call(a18=7) == g.GRAFT_ERR_DTYPE
+    assert call(a15=96) == g.GRAFT_ERR_SHAPE              # D
+    assert call(a14=5) == g.GRAFT_ERR_SHAPE               # Hq % Hkv
+    assert call(a14=1) == g.GRAFT_ERR_SHAPE               # group of 32 > 16
+    assert call(a12=g.GRAFT_MAX_NODES + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a16=32) == g.GRAFT_ERR_SHAPE              # page size
+    assert call(a4=100) == g.GRAFT_ERR_SHAPE              # token stride < D
+    assert call(a4=132) == g.GRAFT_ERR_SHAPE              # token stride not a multiple of 8
+    assert call(a17=0.0) == g.GRAFT_ERR_SHAPE             # scale
+    assert call(a20=None) == g.GRAFT_ERR_WORKSPACE
+    assert call(a21=16) == g.GRAFT_ERR_WORKSPACE
+    need = ws(1, 40, 32, 8, 128, 130, g.GRAFT_BF16)
+    assert need > 0 and need % 8 == 0
+    assert ws(1, 16, 8, 2, 64, 17, g.GRAFT_F32) == 0      # the fp32 path needs no scratch
+    assert ws(1, 40, 32, 8, 96, 130, g.GRAFT_BF16) == 0   # unsupported shape -> 0
+    # more sequences never need less workspace
+    assert ws(4, 96, 32, 8, 128, 4102, g.GRAFT_BF16) >= ws(1, 96, 32, 8, 128, 4102, g.GRAFT_BF16)
+
+
+def test_accept_validation(lib):
+    import paper_2605_20104_amd as g
+    f = lib.graft_accept
+    ok = [P, P, P, None, 0, P, 1, 16, 8, P, P, P, P, P, None, 0, None]
+
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return f(*a)
+    assert call(a0=None) == g.GRAFT_ERR_NULL
+    assert call(a5=None) == g.GRAFT_ERR_NULL
+    assert call(a7=0) == g.GRAFT_ERR_SHAPE
+    assert call(a7=g.GRAFT_MAX_NODES + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a8=-1) == g.GRAFT_ERR_SHAPE
+    assert call(a8=g.GRAFT_MAX_NODES) == g.GRAFT_ERR_SHAPE
+    assert call(a3=P, a4=0) == g.GRAFT_ERR_SHAPE          # logits with V = 0
+    assert call(a3=P, a4=1000) == g.GRAFT_ERR_WORKSPACE   # logits mode needs the workspace
+    assert call(a3=P, a4=1000, a14=P, a15=8) == g.GRAFT_ERR_WORKSPACE
+    assert lib.graft_accept_workspace_bytes(1, 16, 1000) == 16 * 16 * 8
+
+
+def test_binding_has_no_fallback(monkeypatch):
+    import paper_2605_20104_amd as g
+    monkeypatch.setattr(g, "_lib", None)
+    monkeypatch.setattr(g, "LIB_PATH", "/nonexistent/libgraft.so")
+    with pytest.raises(FileNotFoundError):
+        g.load_library()

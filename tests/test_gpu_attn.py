@@ -1,0 +1,183 @@
+"""GPU parity: graft_tree_attn vs the CPU oracle (MI355X only).
+
+Tolerances: bf16 storage with fp32 accumulation must be within 2e-2 max-abs of the
+fp64 oracle (outputs compared in fp32); the fp32 path within 1e-4.
+"""
+import dataclasses
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import inputs
+import oracle
+import paper_2605_20104_amd as graft
+from gpu_util import dev, host, run_attn
+
+pytestmark = pytest.mark.gpu
+TOL_BF16 = 2e-2
+TOL_F32 = 1e-4
+
+
+def gpu_mask(parent, n_nodes, prefix):
+    out = graft.graft_build_tree_mask(dev(parent), dev(n_nodes), dev(prefix))
+    return out["mask"]
+
+
+def shape_workload(B, K, Hq, Hkv, D, P, dtype="bf16"):
+    base = inputs.get_workload("c2")
+    return dataclasses.replace(base, name="t", index=9, B=B, K=K, Hq=Hq, Hkv=Hkv, D=D, P=P, dtype=dtype,
+                               distinct_kv_layers=1)
+
+
+def check_case(w, seed, layout="head_major", n_nodes=None, prefix=None, tol=TOL_BF16, max_depth=8,
+               rows=None):
+    rng = np.random.default_rng(seed)
+    att = inputs.make_attention_inputs(w, seed=seed, layout=layout)
+    parent = np.stack([inputs.random_recursive_tree(rng, w.K, max_depth) for _ in range(w.B)])
+    n_nodes = np.full(w.B, w.K, np.int32) if n_nodes is None else np.asarray(n_nodes, np.int32)
+    prefix = np.full(w.B, w.P, np.int32) if prefix is None else np.asarray(prefix, np.int32)
+    mask = gpu_mask(parent, n_nodes, prefix)
+    got = run_attn(att, w.dtype, prefix, n_nodes, mask, w.Hkv)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], w.dtype, att["strides"],
+                           att["block_table"], prefix, n_nodes, parent, w.Hq, w.Hkv, w.D, w.page_size,
+                           att["scale"], rows=rows)
+    if rows is None:
+        err = np.abs(got - ref.astype(np.float32)).max()
+    else:
+        sel = np.stack([got[b, i, h] for b, i, h in rows])
+        err = np.abs(sel - ref.astype(np.float32)).max()
+    assert np.isfinite(got).all()
+    assert err <= tol, "max abs err %.3e > %.1e" % (err, tol)
+    return got, ref, err
+
+
+def test_c1_fp32_full():
+    w = inputs.get_workload("c1")
+    s = inputs.make_step_inputs(w)
+    att = inputs.make_attention_inputs(w)
+    mask = gpu_mask(s["parent"], s["n_nodes"], s["prefix_len"])
+    got = run_attn(att, "f32", s["prefix_len"], s["n_nodes"], mask, w.Hkv)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "f32", att["strides"],
+                           att["block_table"], s["prefix_len"], s["n_nodes"], s["parent"], w.Hq, w.Hkv, w.D,
+                           w.page_size, att["scale"])
+    assert np.abs(got - ref.astype(np.float32)).max() <= TOL_F32
+
+
+# (B, K, Hq, Hkv, P): chosen to hit every (row blocks per wavefront) variant of the MFMA kernel,
+# both mask words, ragged prefixes (not a multiple of 16, 32 or 64), and several KV splits.
+MFMA_CASES = [
+    (1, 1, 1, 1, 0),          # a lone root, empty prefix
+    (1, 1, 8, 8, 5),
+    (2, 16, 8, 2, 333),       # R = 64
+    (1, 40, 32, 8, 1000),     # R = 160 (config 2 shape, shorter prefix)
+    (1, 64, 40, 8, 777),      # R = 320 (config 3 shape): 3 + 2 row blocks
+    (2, 48, 32, 2, 300),      # R = 768 (config 4 group size 16): two row tiles
+    (1, 96, 8, 2, 1201),      # R = 384 (config 5 shape)
+    (1, 128, 4, 2, 130),      # K = 128: both mask words
+    (3, 33, 6, 2, 64),        # odd sizes, prefix exactly one stage
+    (1, 20, 16, 16, 31),      # group size 1
+]
+
+
+@pytest.mark.parametrize("case", MFMA_CASES, ids=lambda c: "B%d_K%d_Hq%d_Hkv%d_P%d" % c)
+def test_bf16_mfma_shapes(case):
+    B, K, Hq, Hkv, P = case
+    w = shape_workload(B, K, Hq, Hkv, 128, P)
+    check_case(w, seed=1000 + K + P)
+
+
+def test_bf16_ragged_batch_and_padding_nodes():
+    w = shape_workload(4, 48, 16, 4, 128, 500)
+    n_nodes = [48, 1, 17, 33]
+    prefix = [500, 0, 123, 17]
+    got, _, _ = check_case(w, seed=5, n_nodes=n_nodes, prefix=prefix)
+    for b, n in enumerate(n_nodes):
+        assert (got[b, n:] == 0).all()                  # padding rows are zeros
+
+
+def test_bf16_token_major_layout_and_deep_chain():
+    w = shape_workload(2, 64, 8, 2, 128, 200)
+    check_case(w, seed=6, layout="token_major", max_depth=63)
+
+
+def test_bf16_invalid_tree_size_gives_zeros():
+    w = shape_workload(2, 16, 8, 2, 128, 100)
+    got, _, _ = check_case(w, seed=7, n_nodes=[0, 16])
+    assert (got[0] == 0).all()
+
+
+def test_bf16_head_dim_64_and_fp32_head_dim_128():
+    check_case(shape_workload(2, 12, 8, 4, 64, 90), seed=8)
+    check_case(shape_workload(1, 9, 4, 2, 128, 70, dtype="f32"), seed=9, tol=TOL_F32)
+    check_case(shape_workload(2, 12, 8, 4, 64, 600, dtype="f32"), seed=10, tol=TOL_F32)
+
+
+def test_mfma_matches_plain_kernel_on_gpu():
+    """Cross-check of the two GPU paths: same bf16 inputs through the MFMA kernel and, widened to
+    fp32, through the plain kernel."""
+    w = shape_workload(1, 24, 8, 2, 128, 450)
+    got, ref, _ = check_case(w, seed=11)
+    att = inputs.make_attention_inputs(w, seed=11)
+    wide = dict(att, q=[inputs.bf16_bits_to_f32(att["q"][0])],
+                k_cache=[inputs.bf16_bits_to_f32(att["k_cache"][0])],
+                v_cache=[inputs.bf16_bits_to_f32(att["v_cache"][0])])
+    rng = np.random.default_rng(11)
+    parent = np.stack([inputs.random_recursive_tree(rng, w.K, 8)])
+    mask = gpu_mask(parent, [w.K], [w.P])
+    plain = run_attn(wide, "f32", np.array([w.P], np.int32), np.array([w.K], np.int32), mask, w.Hkv)
+    assert np.abs(plain - ref.astype(np.float32)).max() <= TOL_F32
+    assert np.abs(plain - got).max() <= TOL_BF16
+
+
+def test_large_scores_stay_finite():
+    """Peaked softmax (large |q.k|): the lazy running max must not overflow."""
+    w = shape_workload(1, 16, 8, 2, 128, 400)
+    att = inputs.make_attention_inputs(w, seed=12)
+    qf = inputs.bf16_bits_to_f32(att["q"][0]) * 6.0
+    att["q"] = [inputs.f32_to_bf16_bits(qf)]
+    rng = np.random.default_rng(12)
+    parent = np.stack([inputs.random_recursive_tree(rng, w.K, 8)])
+    mask = gpu_mask(parent, [w.K], [w.P])
+    got = run_attn(att, "bf16", np.array([w.P], np.int32), np.array([w.K], np.int32), mask, w.Hkv)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
+                           att["block_table"], [w.P], [w.K], parent, w.Hq, w.Hkv, w.D, 16, att["scale"])
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref.astype(np.float32)).max() <= 4e-2      # bf16 rounding of O(4) outputs
+
+
+def test_c2_full_size_all_rows():
+    w = inputs.get_workload("c2")
+    s = inputs.make_step_inputs(w)
+    att = inputs.make_attention_inputs(w, kv_buffers=1)
+    mask = gpu_mask(s["parent"], s["n_nodes"], s["prefix_len"])
+    got = run_attn(att, "bf16", s["prefix_len"], s["n_nodes"], mask, w.Hkv)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
+                           att["block_table"], s["prefix_len"], s["n_nodes"], s["parent"], w.Hq, w.Hkv, w.D,
+                           16, att["scale"])
+    assert np.abs(got - ref.astype(np.float32)).max() <= TOL_BF16
+
+
+@pytest.mark.parametrize("name,n_rows", [("c3", 96), ("c4", 96), ("c5", 48)])
+def test_full_size_sampled_rows(name, n_rows):
+    """Full benchmark sizes in the benchmark's launch configuration; the oracle computes a
+    seeded sample of (sequence, node, head) rows, always including deep nodes."""
+    w = inputs.get_workload(name)
+    s = inputs.make_step_inputs(w)
+    att = inputs.make_attention_inputs(w, kv_buffers=1)
+    mask = gpu_mask(s["parent"], s["n_nodes"], s["prefix_len"])
+    got = run_attn(att, "bf16", s["prefix_len"], s["n_nodes"], mask, w.Hkv)
+    rng = np.random.default_rng(w.index)
+    rows = np.stack([rng.integers(0, w.B, n_rows), rng.integers(0, w.K, n_rows),
+                     rng.integers(0, w.Hq, n_rows)], axis=1).astype(np.int32)
+    rows[0] = (0, 0, 0)
+    rows[1] = (w.B - 1, w.K - 1, w.Hq - 1)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
+                           att["block_table"], s["prefix_len"], s["n_nodes"], s["parent"], w.Hq, w.Hkv, w.D,
+                           16, att["scale"], rows=rows)
+    sel = np.stack([got[b, i, h] for b, i, h in rows])
+    assert np.isfinite(got).all()
+    assert np.abs(sel - ref.astype(np.float32)).max() <= TOL_BF16
+    # property that holds at any size: every output is a convex combination of V rows
+    assert np.abs(got).max() <= 6.5
