@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid-tree verification step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+    graft_retrieve -> graft_build_tree_mask -> layers x graft_tree_attn -> graft_accept
+on one stream, inputs resident in HBM.  Prints ONE JSON line:
+  metric / value : tree-verify attention algorithmic bytes per step divided by the whole
+                   step's time (GB/s), plus us per step in extra keys;
+  roofline       : the dominant kernel (the MFMA tree-attention kernel) timed with HIP
+                   events recorded by the library right around that kernel;
+  cpu_baseline   : the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 peak
+MALL_BYTES = 256 << 20         # Infinity Cache: KV buffers are rotated to exceed it
+
+
+class Hip:
+    """The few HIP runtime calls the benchmark needs for its own event timing."""
+
+    def __init__(self):
+        self.lib = ctypes.CDLL("libamdhip64.so")
+        self.lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.lib.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.lib.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def event(self):
+        e = ctypes.c_void_p()
+        assert self.lib.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def record(self, e, stream):
+        assert self.lib.hipEventRecord(e, ctypes.c_void_p(stream)) == 0
+
+    def elapsed_ms(self, a, b):
+        assert self.lib.hipEventSynchronize(b) == 0
+        ms = ctypes.c_float()
+        assert self.lib.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return float(ms.value)
+
+
+def attention_bytes_and_flops(w):
+    """Algorithmic traffic of one attention layer: K and V read once, Q read, O written, block table."""
+    e = 2 if w.dtype == "bf16" else 4
+    T = w.P + w.K
+    kv = 2 * T * w.Hkv * w.D * e
+    qo = 2 * w.K * w.Hq * w.D * e
+    table = 4 * ((T + w.page_size - 1) // w.page_size)
+    return w.B * (kv + qo + table), 4.0 * w.K * w.Hq * w.D * T * w.B
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import inputs
+    import paper_2605_20104_amd as graft
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    graft.load_library()                       # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    hip = Hip()
+
+    w = inputs.get_workload(args.workload)
+    steps = args.steps if args.steps is not None else {"c1": 200, "c2": 100, "c3": 100, "c4": 20, "c5": 30}[w.name]
+    warmup = args.warmup if args.warmup is not None else 10
+    att_bytes, att_flops = attention_bytes_and_flops(w)
+
+    # ---- inputs -> HBM
+    s = inputs.make_step_inputs(w)
+    kv_bytes_one = att_bytes  # per layer
+    n_kv = max(w.distinct_kv_layers, 1)
+    while n_kv * kv_bytes_one < 2 * MALL_BYTES and n_kv < 64 and w.name != "c1":
+        n_kv += 1                              # rotate buffers so that every launch streams from HBM
+    att = inputs.make_attention_inputs(w, kv_buffers=n_kv, q_layers=min(w.layers, 4))
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    def up(a, kind="i32"):
+        if kind == "store":
+            if w.dtype == "bf16":
+                return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+            return torch.from_numpy(a).cuda()
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+    d = {k: up(s[k]) for k in ("ctx", "ctx_len", "tail", "tail_len", "parent", "tokens", "n_nodes",
+                               "prefix_len", "target_ids")}
+    q = [up(att["q"][l], "store") for l in range(att["q"].shape[0])]
+    kc = [up(a, "store") for a in att["k_cache"]]
+    vc = [up(a, "store") for a in att["v_cache"]]
+    table = up(att["block_table"])
+    B, K = w.B, w.K
+    dev = "cuda"
+    ret_out = {
+        "chain_tok": torch.empty((B, w.C, w.m), dtype=torch.int32, device=dev),
+        "chain_len": torch.empty((B, w.C), dtype=torch.int32, device=dev),
+        "chain_pos": torch.empty((B, w.C), dtype=torch.int32, device=dev),
+        "chain_match": torch.empty((B, w.C), dtype=torch.int32, device=dev),
+        "n_hits": torch.empty(B, dtype=torch.int32, device=dev),
+        "status": torch.empty(B, dtype=torch.int32, device=dev),
+    }
+    depth_cap = 48
+    mask_out = {
+        "mask": torch.empty((B, K, 2), dtype=torch.int64, device=dev),
+        "pos": torch.empty((B, K), dtype=torch.int32, device=dev),
+        "depth": torch.empty((B, K), dtype=torch.int32, device=dev),
+        "paths": torch.empty((B, K, depth_cap + 1), dtype=torch.int32, device=dev),
+        "status": torch.empty(B, dtype=torch.int32, device=dev),
+    }
+    acc_out = {
+        "accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+        "best_node": torch.empty(B, dtype=torch.int32, device=dev),
+        "path": torch.empty((B, depth_cap + 1), dtype=torch.int32, device=dev),
+        "out_tokens": torch.empty((B, depth_cap + 1), dtype=torch.int32, device=dev),
+        "status": torch.empty(B, dtype=torch.int32, device=dev),
+    }
+    o = torch.empty((B, K, w.Hq, w.D), dtype=tdt, device=dev)
+    ws_bytes = graft.graft_tree_attn_workspace_bytes(B, K, w.Hq, w.Hkv, w.D, table.shape[1],
+                                                     graft.GRAFT_BF16 if w.dtype == "bf16" else graft.GRAFT_F32)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    layer_counter = [0]
+
+    def step():
+        graft.graft_retrieve(d["ctx"], d["ctx_len"], w.n_min, w.n_max, w.C, w.m, d["tail"], d["tail_len"],
+                             out=ret_out)
+        graft.graft_build_tree_mask(d["parent"], d["n_nodes"], d["prefix_len"], K, depth_cap, out=mask_out)
+        for l in range(w.layers):
+            i = layer_counter[0]
+            layer_counter[0] += 1
+            graft.graft_tree_attn(q[l % len(q)], kc[i % n_kv], vc[i % n_kv], att["strides"], table,
+                                  d["prefix_len"], d["n_nodes"], mask_out["mask"], w.Hkv, att["scale"],
+                                  out=o, workspace=ws)
+        graft.graft_accept(d["parent"], d["tokens"], d["n_nodes"], depth_cap, target_ids=d["target_ids"],
+                           out=acc_out)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` steps; the library records an event pair around every
+    #      main attention kernel in it
+    n_ev = steps * w.layers
+    ev_a = (ctypes.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)])
+    ev_b = (ctypes.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)])
+    lib = graft.load_library()
+    assert lib.graft_attn_profile_events(ev_a, ev_b, n_ev) == 0
+    t_a, t_b = hip.event(), hip.event()
+    torch.cuda.synchronize()
+    hip.record(t_a, stream)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    hip.record(t_b, stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    total_ms = hip.elapsed_ms(t_a, t_b)
+    lib.graft_attn_profile_events(None, None, 0)
+    kern_ms = np.array([hip.elapsed_ms(ev_a[i], ev_b[i]) for i in range(n_ev)])
+    ms_per_step = total_ms / steps
+    kernel_avg_ms = float(kern_ms.mean())
+
+    # ---- per-call timings (separate, untimed-region loop): median over a few repetitions
+    def time_call(fn, reps=20):
+        ts = []
+        for _ in range(reps):
+            a, b = hip.event(), hip.event()
+            hip.record(a, stream)
+            fn()
+            hip.record(b, stream)
+            ts.append(hip.elapsed_ms(a, b) * 1e3)
+        return float(np.median(ts))
+
+    per_call_us = {
+        "retrieve": time_call(lambda: graft.graft_retrieve(d["ctx"], d["ctx_len"], w.n_min, w.n_max, w.C, w.m,
+                                                            d["tail"], d["tail_len"], out=ret_out)),
+        "build_tree_mask": time_call(lambda: graft.graft_build_tree_mask(
+            d["parent"], d["n_nodes"], d["prefix_len"], K, depth_cap, out=mask_out)),
+        "tree_attn_layer": time_call(lambda: graft.graft_tree_attn(
+            q[0], kc[layer_counter[0] % n_kv], vc[layer_counter[0] % n_kv], att["strides"], table,
+            d["prefix_len"], d["n_nodes"], mask_out["mask"], w.Hkv, att["scale"], out=o, workspace=ws)),
+        "accept": time_call(lambda: graft.graft_accept(d["parent"], d["tokens"], d["n_nodes"], depth_cap,
+                                                       target_ids=d["target_ids"], out=acc_out)),
+    }
+
+    # ---- sanity of the timed outputs against the generator's planted answers
+    torch.cuda.synchronize()
+    pos = ret_out["chain_pos"].cpu().numpy()
+    for b in range(B):
+        assert pos[b].tolist() == s["planted_pos"][b][:w.C], "retrieval lost the planted chains"
+    assert torch.isfinite(o.float()).all()
+
+    step_att_bytes = att_bytes * w.layers
+    value = step_att_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = att_bytes / (kernel_avg_ms * 1e-3) / 1e9
+    mfma_tflops = att_flops / (kernel_avg_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % w.name)
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("traffic_bytes_per_launch")
+
+    result = {
+        "metric": "tree-verify attention HBM GB/s (% of peak) + retrieve+verify us/step",
+        "value": round(value, 2), "unit": "GB/s",
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "us_per_step": round(ms_per_step * 1e3, 2),
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
+        "host_wall_ms_per_step": round(wall * 1e3 / steps, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {
+            "workload": "%s: B=%d, prefix=%d, tree nodes=%d, Hq/Hkv/D=%d/%d/%d, layers=%d, paged KV block 16"
+                        % (w.name, w.B, w.P, w.K, w.Hq, w.Hkv, w.D, w.layers),
+            "step": "graft_retrieve + graft_build_tree_mask + %d x graft_tree_attn + graft_accept(target_ids)" % w.layers,
+            "kv_buffers_rotated": n_kv, "context_len": w.L, "vocab": w.vocab,
+            "attention_bytes_per_layer": att_bytes, "attention_flops_per_layer": att_flops,
+        },
+        "per_call_us": {k: round(v, 2) for k, v in per_call_us.items()},
+        "roofline": {
+            "kernel": "tree_attn_mfma_kernel" if (w.dtype == "bf16" and w.D == 128) else "tree_attn_simple_kernel",
+            "bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "kernel_avg_us": round(kernel_avg_ms * 1e3, 3), "launches_timed": n_ev,
+            "mfma_tflops": round(mfma_tflops, 2), "mfma_frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+            "arithmetic_intensity_flop_per_byte": round(att_flops / att_bytes, 1),
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, s, att, att_bytes, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, s, att, att_bytes, budget_s):
+    """The oracle, as it stands, timed on the host: integer steps in full, attention on a
+    seeded sample of (sequence, node, head) rows sized to the time budget, scaled to one step."""
+    import oracle
+    t0 = time.perf_counter()
+    oracle.retrieve(s["ctx"], s["ctx_len"], w.n_min, w.n_max, w.C, w.m, s["tail"], s["tail_len"])
+    oracle.build_tree_mask(s["parent"], s["n_nodes"], s["prefix_len"], w.K, 48)
+    oracle.accept(s["parent"], s["tokens"], s["n_nodes"], 48, target_ids=s["target_ids"])
+    t_int = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0))
+    omp = os.environ.get("OMP_NUM_THREADS")
+    threads = min(cores, int(omp)) if omp else cores
+    total_rows = w.B * w.K * w.Hq
+    rng = np.random.default_rng(1)
+
+    def run(n):
+        rows = np.stack([rng.integers(0, w.B, n), rng.integers(0, w.K, n), rng.integers(0, w.Hq, n)],
+                        axis=1).astype(np.int32)
+        t = time.perf_counter()
+        oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], w.dtype, att["strides"],
+                         att["block_table"], s["prefix_len"], s["n_nodes"], s["parent"], w.Hq, w.Hkv, w.D,
+                         w.page_size, att["scale"], rows=rows)
+        return time.perf_counter() - t
+    n = min(total_rows, 4 * threads)
+    t = run(n)
+    per_row = t / n
+    n2 = int(min(total_rows, max(n, budget_s / max(per_row, 1e-9))))
+    t2 = run(n2)
+    per_row = t2 / n2
+    est_step = t_int + per_row * total_rows * w.layers
+    return {
+        "value": round(att_bytes * w.layers / est_step / 1e9, 4), "unit": "GB/s",
+        "cores": threads, "kind": "oracle",
+        "sample": "integer steps in full (%.4f s) + attention on %d of %d (sequence,node,head) rows of one layer "
+                  "(%.2f s), scaled to %d layers: %.1f s per step" % (t_int, n2, total_rows, t2, w.layers, est_step),
+        "est_seconds_per_step": round(est_step, 3),
+    }
+
+
+if __name__ == "__main__":
+    main()

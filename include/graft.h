@@ -182,6 +182,17 @@ int32_t graft_tree_attn(const void* q, const void* k_cache, const void* v_cache,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * graft_attn_profile_events - measurement hook for benchmarks (not part of the
+ * method).  start_events / stop_events are host arrays of n hipEvent_t created by
+ * the caller.  While set, the i-th graft_tree_attn call made afterwards on this
+ * host thread (i < n) records start_events[i] on the stream right before its main
+ * attention kernel and stop_events[i] right after it (before the split-merge
+ * kernel), so the caller can read that kernel's own duration.  n = 0 clears the
+ * hook.  The arrays must stay alive until it is cleared.
+ */
+int32_t graft_attn_profile_events(void** start_events, void** stop_events, int32_t n);
+
+/*
  * graft_accept - the acceptance step under greedy decoding: the unchanged
  * speculative rule (Sec. 3.3; App. A Alg. 1 "select the accepted path";
  * App. B.4) specialised to the greedy setting of the main results (Sec. 4).

@@ -38,6 +38,7 @@ _SIGNATURES = {
     "graft_tree_attn_workspace_bytes": (_sz, [_i32] * 7),
     "graft_tree_attn": (_i32, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _vp,
                                _i32, _i32, _i32, _i32, _i32, _i32, _f32, _i32, _vp, _vp, _sz, _vp]),
+    "graft_attn_profile_events": (_i32, [_vp, _vp, _i32]),
     "graft_accept_workspace_bytes": (_sz, [_i32] * 3),
     "graft_accept": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32,
                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),

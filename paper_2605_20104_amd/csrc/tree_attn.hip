@@ -92,7 +92,7 @@ __device__ __forceinline__ void attn_subtile(
     const unsigned char* __restrict__ Ks, const unsigned char* __restrict__ Vs,
     const bf16x8 (&qreg)[MB][4], floatx4 (&o)[MB][8], float (&m_run)[MB], float (&l_run)[MB],
     float c_log2, float lazy_raw, int lane,
-    bool masked, int t_sub0, int P, int n, int r_base, int R, int G, const u64* __restrict__ Ms) {
+    bool masked, int t_sub0, int P, int n, int r_base, int R, int G, const unsigned* __restrict__ Ms) {
     const int l16 = lane & 15, lg = lane >> 4;
 
     // ---- S^T = K Q^T : s[rb][c][i] = score of row (rb, l16) and token 16c + 4lg + i
@@ -119,21 +119,26 @@ __device__ __forceinline__ void attn_subtile(
     bf16x8 pb[MB];
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) {
-        if (masked) {                                     // wavefront-uniform
+        if (masked) {                                     // wavefront-uniform; branch-free inside
             const int r = r_base + rb * 16 + l16;
             const int node = r / G;
-            u64 mk0 = 0, mk1 = 0;
-            if (r < R && node < n) { mk0 = Ms[2 * node]; mk1 = Ms[2 * node + 1]; }
+            const bool live = r < R && node < n;
+            const int nd = live ? node : 0;
+            const unsigned w0 = live ? Ms[4 * nd + 0] : 0u, w1 = live ? Ms[4 * nd + 1] : 0u;
+            const unsigned w2 = live ? Ms[4 * nd + 2] : 0u, w3 = live ? Ms[4 * nd + 3] : 0u;
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+            for (int c = 0; c < 2; ++c) {
+                const int j0 = t_sub0 + 16 * c + 4 * lg - P;          // tree slot of element i = 0
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int t = t_sub0 + 16 * c + 4 * lg + i;
-                    const int j = t - P;
-                    bool valid = j < 0;
-                    if (j >= 0 && j < n) valid = ((j < 64 ? mk0 : mk1) >> (j & 63)) & 1ull;
-                    if (!valid) s[rb][c][i] = -INFINITY;
+                    const int j = j0 + i;
+                    const int wi = (j >> 5) & 3;
+                    const unsigned word = wi == 0 ? w0 : (wi == 1 ? w1 : (wi == 2 ? w2 : w3));
+                    const bool bit = (word >> (j & 31)) & 1u;
+                    const bool valid = (j < 0) | ((j < n) & bit);
+                    s[rb][c][i] = valid ? s[rb][c][i] : -INFINITY;
                 }
+            }
         }
         float mx = fmaxf(fmaxf(fmaxf(s[rb][0][0], s[rb][0][1]), fmaxf(s[rb][0][2], s[rb][0][3])),
                          fmaxf(fmaxf(s[rb][1][0], s[rb][1][1]), fmaxf(s[rb][1][2], s[rb][1][3])));
@@ -189,46 +194,93 @@ __device__ __forceinline__ void attn_subtile(
 
 struct SplitRange { int st0, st1, P, n, total; };
 
+constexpr int AT_MAX_SPLIT_PAGES = 4096;          // block-table entries of one split kept in LDS
+constexpr int AT_NBUF = 4;                         // LDS stage buffers: 3 stages in flight + 1 in use
+constexpr int AT_STAGE_BYTES = 2 * AT_STAGE * AT_ROW_BYTES;   // K rows then V rows
+constexpr int AT_LOADS_PER_STAGE = 4;              // global->LDS instructions per wavefront per stage
+
 // Global -> LDS without passing through registers: each lane's 16 bytes land at
 // (wavefront-uniform LDS base) + lane * 16, so the swizzled LDS layout is produced by
 // choosing which global chunk each lane fetches.  One wavefront moves 4 token rows
-// (1 KB) of K or of V per instruction; 8 wavefronts x 2 instructions = one 64-token stage.
-__device__ __forceinline__ void stage_loads(const AttnParams& p, const SplitRange& sr, int st, int wave,
-                                            int lane, const int32_t* __restrict__ table, int g,
-                                            unsigned char* Kbuf, unsigned char* Vbuf) {
+// (1 KB) of K or of V per instruction; 8 wavefronts x 2 x (K,V) = one 64-token stage.
+// The block-table entries of the split were copied to LDS (Tb) up front, so the lookup is
+// an LDS read and nothing but the transfers themselves occupies the vector memory counter.
+//
+// The transfer is issued through inline assembly on purpose: the kernel keeps several stages
+// in flight and waits for them with explicit s_waitcnt vmcnt(N); transfers the compiler knows
+// about make it drain the whole vector memory counter before every LDS read and barrier.
+__device__ __forceinline__ void load_global_to_lds_b128(const void* gptr, unsigned lds_addr) {
+    // LDS address of lane l = M0 + 16 * l (M0 write needs one wait state before its use).
+    // M0 is a reserved register the compiler sets up itself right before each of its own uses.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(gptr)
+                 : "memory");
+}
+
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+    return static_cast<unsigned>(reinterpret_cast<size_t>(
+        (const __attribute__((address_space(3))) unsigned char*)(p)));
+}
+
+__device__ __forceinline__ void stage_loads(const AttnParams& p, const SplitRange& sr, int st, int wave_u,
+                                            int lane, const int32_t* __restrict__ Tb, int g,
+                                            unsigned char* buf) {
     const int l16 = lane & 15;
+    const unsigned lds_base = __builtin_amdgcn_readfirstlane(lds_address(buf));
+    const int last = sr.total - 1;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const int row = 4 * (2 * wave + j) + (lane >> 4);        // token row within the stage
+        const int slot = 2 * wave_u + j;                         // 1 KB slot = 4 token rows
+        const int row = 4 * slot + (lane >> 4);                  // token row within the stage
+        const int pg = (st - sr.st0) * (AT_STAGE / GRAFT_PAGE_SIZE) + (slot >> 2);   // uniform, split-local
         int t = st * AT_STAGE + row;
-        t = t < sr.total ? t : sr.total - 1;                     // rows past the end re-read the last token
-        const int64_t off = static_cast<int64_t>(table[t >> 4]) * p.page_stride +
+        t = t < last ? t : last;                                 // rows past the end re-read the last token
+        const int64_t off = static_cast<int64_t>(Tb[pg]) * p.page_stride +
                             static_cast<int64_t>(t & 15) * p.token_stride +
                             static_cast<int64_t>(g) * p.head_stride;
         const int kchunk = l16 ^ (row & 15);
         const int vchunk = (((l16 >> 1) ^ (row & 7)) << 1) | (l16 & 1);
         const __bf16* ksrc = static_cast<const __bf16*>(p.k) + off + kchunk * 8;
         const __bf16* vsrc = static_cast<const __bf16*>(p.v) + off + vchunk * 8;
-        __builtin_amdgcn_global_load_lds(ksrc, (__attribute__((address_space(3))) void*)(Kbuf + (2 * wave + j) * 1024),
-                                         16, 0, 0);
-        __builtin_amdgcn_global_load_lds(vsrc, (__attribute__((address_space(3))) void*)(Vbuf + (2 * wave + j) * 1024),
-                                         16, 0, 0);
+        const unsigned lds = lds_base + slot * 1024;
+        load_global_to_lds_b128(ksrc, lds);
+        load_global_to_lds_b128(vsrc, lds + AT_STAGE * AT_ROW_BYTES);
     }
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also drain the
+// vector memory counter and with it the global->LDS transfers of the stages still in flight.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt fields left at "no wait")
+#define GRAFT_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
+
 template <int MB>
 __device__ __forceinline__ void attn_wave_main(const AttnParams& p, const SplitRange& sr, int r_base,
-                                               int split, int g, int b, unsigned char (*Ks)[AT_STAGE * AT_ROW_BYTES],
-                                               unsigned char (*Vs)[AT_STAGE * AT_ROW_BYTES],
-                                               const u64* __restrict__ Ms) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+                                               int split, int g, int b, unsigned char* kv0, unsigned char* kv1,
+                                               unsigned char* kv2, unsigned char* kv3,
+                                               const unsigned* __restrict__ Ms, const int32_t* __restrict__ Tb) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lg = lane >> 4;
-    const int32_t* table = p.block_table + static_cast<size_t>(b) * p.max_pages;
+    constexpr int MBX = MB > 0 ? MB : 1;
+
+    unsigned char* const bufs[AT_NBUF] = {kv0, kv1, kv2, kv3};
+    const int n_st = sr.st1 - sr.st0;
+    // pipeline prologue: the first three stages start streaming before anything else
+#pragma unroll
+    for (int k = 0; k < AT_NBUF - 1; ++k)
+        if (k < n_st) stage_loads(p, sr, sr.st0 + k, wave_u, lane, Tb, g, bufs[k]);
 
     // ---- Q rows of this wavefront stay in registers (B operand of S^T = K Q^T)
-    bf16x8 qreg[MB > 0 ? MB : 1][4];
-    floatx4 o[MB > 0 ? MB : 1][8];
-    float m_run[MB > 0 ? MB : 1], l_run[MB > 0 ? MB : 1];
+    bf16x8 qreg[MBX][4];
+    floatx4 o[MBX][8];
+    float m_run[MBX], l_run[MBX];
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) {
         const int r = r_base + rb * 16 + l16;
@@ -250,31 +302,41 @@ __device__ __forceinline__ void attn_wave_main(const AttnParams& p, const SplitR
         for (int db = 0; db < 8; ++db) o[rb][db] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // Q must have landed before the loop: a pending compiler-tracked load would make every
+    // iteration drain the vector memory counter (and the stages in flight with it).
+    GRAFT_WAIT_VMCNT(0);
     const float c_log2 = p.scale_log2e;
     const float lazy_raw = AT_LAZY_LOG2 / c_log2;
 
-    if (sr.st0 < sr.st1) {
-        stage_loads(p, sr, sr.st0, wave, lane, table, g, Ks[0], Vs[0]);
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        int buf = 0;
-        for (int st = sr.st0; st < sr.st1; ++st) {
-            if (st + 1 < sr.st1) stage_loads(p, sr, st + 1, wave, lane, table, g, Ks[buf ^ 1], Vs[buf ^ 1]);
+    // ---- software pipeline over 64-token stages: stage k lives in buffer k % 4, loads run
+    //      three stages ahead; before a stage is used every wavefront waits for its own
+    //      loads of that stage (the younger stages' loads stay in flight) and meets the
+    //      others at one barrier, which also frees the buffer consumed one stage earlier.
+    for (int base = 0; base < n_st; base += AT_NBUF) {
+#pragma unroll
+        for (int i = 0; i < AT_NBUF; ++i) {
+            const int idx = base + i;
+            if (idx >= n_st) break;
+            const int younger = n_st - 1 - idx;                  // stages already issued after this one
+            if (younger >= 2) GRAFT_WAIT_VMCNT(2 * AT_LOADS_PER_STAGE);
+            else if (younger == 1) GRAFT_WAIT_VMCNT(AT_LOADS_PER_STAGE);
+            else GRAFT_WAIT_VMCNT(0);
+            lds_barrier();
+            if (idx + AT_NBUF - 1 < n_st)
+                stage_loads(p, sr, sr.st0 + idx + AT_NBUF - 1, wave_u, lane, Tb, g,
+                            bufs[(i + AT_NBUF - 1) % AT_NBUF]);
             if (MB > 0) {
+                const int st = sr.st0 + idx;
 #pragma unroll 1
                 for (int sub = 0; sub < 2; ++sub) {
                     const int t_sub0 = st * AT_STAGE + sub * AT_SUB;
                     if (t_sub0 < sr.total)
-                        attn_subtile<(MB > 0 ? MB : 1)>(Ks[buf] + sub * AT_SUB * AT_ROW_BYTES,
-                                                        Vs[buf] + sub * AT_SUB * AT_ROW_BYTES, qreg, o, m_run,
-                                                        l_run, c_log2, lazy_raw, lane,
-                                                        t_sub0 + AT_SUB > sr.P, t_sub0, sr.P, sr.n, r_base,
-                                                        p.R, p.G, Ms);
+                        attn_subtile<MBX>(bufs[i] + sub * AT_SUB * AT_ROW_BYTES,
+                                          bufs[i] + AT_STAGE * AT_ROW_BYTES + sub * AT_SUB * AT_ROW_BYTES, qreg, o,
+                                          m_run, l_run, c_log2, lazy_raw, lane, t_sub0 + AT_SUB > sr.P, t_sub0,
+                                          sr.P, sr.n, r_base, p.R, p.G, Ms);
                 }
             }
-            __builtin_amdgcn_s_waitcnt(0);
-            __syncthreads();
-            buf ^= 1;
         }
     }
 
@@ -303,9 +365,14 @@ __device__ __forceinline__ void attn_wave_main(const AttnParams& p, const SplitR
 // count like 320 = 16 * (4*3 + 4*2) is balanced over the four SIMDs.
 template <int MBA, int MBB>
 __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p) {
-    __shared__ __attribute__((aligned(1024))) unsigned char Ks[2][AT_STAGE * AT_ROW_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char Vs[2][AT_STAGE * AT_ROW_BYTES];
-    __shared__ u64 Ms[GRAFT_MAX_NODES * GRAFT_MASK_WORDS];
+    // Four separate arrays on purpose: the compiler tracks pending global->LDS transfers per
+    // LDS variable, so reads of one stage buffer do not wait for transfers into the others.
+    __shared__ __attribute__((aligned(1024))) unsigned char kv0[AT_STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char kv1[AT_STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char kv2[AT_STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char kv3[AT_STAGE_BYTES];
+    __shared__ unsigned Ms[GRAFT_MAX_NODES * GRAFT_MASK_WORDS * 2];   // ancestor masks as 32-bit words
+    __shared__ int32_t Tb[AT_MAX_SPLIT_PAGES];                         // this split's block-table entries
 
     const int tid = threadIdx.x, wave = tid >> 6;
     const int split = blockIdx.x % p.n_splits, rt = blockIdx.x / p.n_splits;
@@ -324,17 +391,28 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     const int spt = (n_stages + p.n_splits - 1) / p.n_splits;
     sr.st0 = split * spt;
     sr.st1 = (sr.st0 + spt) < n_stages ? (sr.st0 + spt) : n_stages;
+    if (sr.st1 < sr.st0) sr.st1 = sr.st0;
 
-    if (tid < p.K_max * GRAFT_MASK_WORDS)
-        Ms[tid] = p.mask[static_cast<size_t>(b) * p.K_max * GRAFT_MASK_WORDS + tid];
-    // (published by the first barrier inside attn_wave_main; read only on masked sub-tiles)
+    if (tid < p.K_max * GRAFT_MASK_WORDS * 2)
+        Ms[tid] = reinterpret_cast<const unsigned*>(p.mask)[static_cast<size_t>(b) * p.K_max * GRAFT_MASK_WORDS * 2 + tid];
+    {
+        const int32_t* table = p.block_table + static_cast<size_t>(b) * p.max_pages;
+        const int first_pg = sr.st0 * (AT_STAGE / GRAFT_PAGE_SIZE);
+        const int n_pg = (sr.st1 - sr.st0) * (AT_STAGE / GRAFT_PAGE_SIZE);
+        const int last_pg = (sr.total - 1) >> 4;
+        for (int k = tid; k < n_pg; k += AT_THREADS) {
+            const int pg = first_pg + k;
+            Tb[k] = table[pg < last_pg ? pg : last_pg];
+        }
+    }
+    __syncthreads();
 
     const int tile_base = rt * (AT_WAVES / 2) * 16 * (MBA + MBB);
     if (wave < AT_WAVES / 2) {
-        attn_wave_main<MBA>(p, sr, tile_base + wave * 16 * MBA, split, g, b, Ks, Vs, Ms);
+        attn_wave_main<MBA>(p, sr, tile_base + wave * 16 * MBA, split, g, b, kv0, kv1, kv2, kv3, Ms, Tb);
     } else {
         attn_wave_main<MBB>(p, sr, tile_base + (AT_WAVES / 2) * 16 * MBA + (wave - AT_WAVES / 2) * 16 * MBB,
-                            split, g, b, Ks, Vs, Ms);
+                            split, g, b, kv0, kv1, kv2, kv3, Ms, Tb);
     }
 }
 
@@ -518,6 +596,8 @@ static AttnPlan make_plan(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
     if (splits > stages) splits = stages;
     if (splits > AT_MAX_SPLITS) splits = AT_MAX_SPLITS;
     if (splits < 1) splits = 1;
+    const int min_splits = (stages * (AT_STAGE / GRAFT_PAGE_SIZE) + AT_MAX_SPLIT_PAGES - 1) / AT_MAX_SPLIT_PAGES;
+    if (splits < min_splits) splits = min_splits;       // a split's block-table slice must fit in LDS
     pl.n_splits = splits;
     const size_t rows = static_cast<size_t>(B) * Hkv * splits * pl.r_pad;
     pl.ws_o_bytes = rows * AT_D * sizeof(float);
@@ -529,6 +609,18 @@ static bool attn_shape_ok(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
     return B >= 1 && B <= 65535 && K_max >= 1 && K_max <= GRAFT_MAX_NODES && Hq >= 1 && Hkv >= 1 &&
            Hkv <= 65535 && Hq % Hkv == 0 && Hq / Hkv <= 16 && (D == 64 || D == 128) && max_pages >= 1 &&
            max_pages <= (1 << 26);
+}
+
+// Profiling hook state (per host thread): event pairs recorded around the main kernel.
+static thread_local hipEvent_t* g_prof_start = nullptr;
+static thread_local hipEvent_t* g_prof_stop = nullptr;
+static thread_local int32_t g_prof_n = 0, g_prof_i = 0;
+
+static void prof_record(bool start, hipStream_t s) {
+    if (g_prof_i < g_prof_n) {
+        (void)hipEventRecord(start ? g_prof_start[g_prof_i] : g_prof_stop[g_prof_i], s);
+        if (!start) ++g_prof_i;
+    }
 }
 
 template <int MBA, int MBB>
@@ -543,6 +635,15 @@ extern "C" size_t graft_tree_attn_workspace_bytes(int32_t B, int32_t K_max, int3
     if (!graft::attn_shape_ok(B, K_max, Hq, Hkv, D, max_pages)) return 0;
     if (dtype != GRAFT_F32 && dtype != GRAFT_BF16) return 0;
     return graft::make_plan(B, K_max, Hq, Hkv, D, max_pages, dtype).ws_bytes;
+}
+
+extern "C" int32_t graft_attn_profile_events(void** start_events, void** stop_events, int32_t n) {
+    if (n < 0 || (n > 0 && (!start_events || !stop_events))) return GRAFT_ERR_NULL;
+    graft::g_prof_start = reinterpret_cast<hipEvent_t*>(start_events);
+    graft::g_prof_stop = reinterpret_cast<hipEvent_t*>(stop_events);
+    graft::g_prof_n = n;
+    graft::g_prof_i = 0;
+    return GRAFT_OK;
 }
 
 extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const void* v_cache,
@@ -576,12 +677,14 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
 
     if (!pl.mfma) {
         dim3 grid(Hq, K_max, B);
+        prof_record(true, s);
         if (dtype == GRAFT_F32) {
             if (D == 64) hipLaunchKernelGGL((tree_attn_simple_kernel<float, 64>), grid, dim3(SM_THREADS), 0, s, p);
             else hipLaunchKernelGGL((tree_attn_simple_kernel<float, 128>), grid, dim3(SM_THREADS), 0, s, p);
         } else {
             hipLaunchKernelGGL((tree_attn_simple_kernel<unsigned short, 64>), grid, dim3(SM_THREADS), 0, s, p);
         }
+        prof_record(false, s);
         return check_launch();
     }
 
@@ -589,6 +692,7 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     p.ws_o = static_cast<float*>(workspace);
     p.ws_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + pl.ws_o_bytes);
     dim3 grid(pl.n_splits * pl.n_row_tiles, Hkv, B);
+    prof_record(true, s);
     switch (pl.mba * 4 + pl.mbb) {
         case 1 * 4 + 0: launch_mfma<1, 0>(p, grid, s); break;
         case 1 * 4 + 1: launch_mfma<1, 1>(p, grid, s); break;
@@ -597,6 +701,7 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
         case 3 * 4 + 2: launch_mfma<3, 2>(p, grid, s); break;
         default: launch_mfma<3, 3>(p, grid, s); break;
     }
+    prof_record(false, s);
     int32_t rc = check_launch();
     if (rc != GRAFT_OK) return rc;
     const int64_t n_rows = static_cast<int64_t>(B) * K_max * Hq;
