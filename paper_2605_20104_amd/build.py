@@ -14,9 +14,11 @@ OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libgraft.so")
 SOURCES = ["api.hip", "retrieve.hip", "tree_mask.hip", "tree_attn.hip", "accept.hip"]
 
-# packed-fp32 code generation is switched off for every device compile
+# packed-fp32 code generation is switched off for every device compile; VGPR spills must not
+# land in AccVGPRs (the attention kernel manages those by hand)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-mllvm", "-amdgpu-spill-vgpr-to-agpr=0",
                "-Wno-unused-command-line-argument"]
 
 

@@ -38,6 +38,8 @@
 // (2) everything else (fp32 storage, or D = 64): a plain one-workgroup-per-
 //     (node, head) kernel in fp32.  It serves the tiny fp32 configuration and as
 //     an independent GPU cross-check of path (1).
+#include <type_traits>
+
 #include "common.h"
 
 namespace graft {
@@ -46,16 +48,17 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 
-constexpr int AT_THREADS = 512;
-constexpr int AT_WAVES = 8;
+constexpr int AT_THREADS = 256;
+constexpr int AT_WAVES = 4;
 constexpr int AT_STAGE = 64;        // tokens per LDS stage (4 pages)
 constexpr int AT_SUB = 32;          // tokens per softmax step
 constexpr int AT_D = 128;
 constexpr int AT_ROW_BYTES = AT_D * 2;
-constexpr int AT_MAX_BLOCKS = 24;      // 16-row blocks per workgroup: 4 * (3 + 3)
+constexpr int AT_MAX_MB = 5;            // 16-row MFMA blocks per wavefront (5 * 48 = 240 of 256 AccVGPRs)
 constexpr int AT_MAX_SPLITS = 64;
-constexpr float AT_LAZY_LOG2 = 8.0f;   // rescale only when the max grows by more than 2^8
+constexpr float AT_LAZY_LOG2 = 24.0f;  // a row keeps its reference while exponents stay below 2^24
 
 struct AttnParams {
     const void* q;
@@ -86,125 +89,17 @@ __device__ __forceinline__ unsigned short float_to_bf16_bits(float f) {
 // ---------------------------------------------------------------------------
 // path (1): MFMA split-KV kernel
 // ---------------------------------------------------------------------------
-// One 32-token sub-tile for the MB row blocks of this wavefront.
-template <int MB>
-__device__ __forceinline__ void attn_subtile(
-    const unsigned char* __restrict__ Ks, const unsigned char* __restrict__ Vs,
-    const bf16x8 (&qreg)[MB][4], floatx4 (&o)[MB][8], float (&m_run)[MB], float (&l_run)[MB],
-    float c_log2, float lazy_raw, int lane,
-    bool masked, int t_sub0, int P, int n, int r_base, int R, int G, const unsigned* __restrict__ Ms) {
-    const int l16 = lane & 15, lg = lane >> 4;
-
-    // ---- S^T = K Q^T : s[rb][c][i] = score of row (rb, l16) and token 16c + 4lg + i
-    floatx4 s[MB][2];
-#pragma unroll
-    for (int rb = 0; rb < MB; ++rb) {
-        s[rb][0] = floatx4{0.f, 0.f, 0.f, 0.f};
-        s[rb][1] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const int row = 16 * c + l16;
-#pragma unroll
-        for (int ds = 0; ds < 4; ++ds) {
-            const int chunk = (4 * ds + lg) ^ l16;
-            const bf16x8 ka = *reinterpret_cast<const bf16x8*>(Ks + row * AT_ROW_BYTES + chunk * 16);
-#pragma unroll
-            for (int rb = 0; rb < MB; ++rb)
-                s[rb][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[rb][ds], s[rb][c], 0, 0, 0);
-        }
-    }
-
-    // ---- online softmax per row block
-    bf16x8 pb[MB];
-#pragma unroll
-    for (int rb = 0; rb < MB; ++rb) {
-        if (masked) {                                     // wavefront-uniform; branch-free inside
-            const int r = r_base + rb * 16 + l16;
-            const int node = r / G;
-            const bool live = r < R && node < n;
-            const int nd = live ? node : 0;
-            const unsigned w0 = live ? Ms[4 * nd + 0] : 0u, w1 = live ? Ms[4 * nd + 1] : 0u;
-            const unsigned w2 = live ? Ms[4 * nd + 2] : 0u, w3 = live ? Ms[4 * nd + 3] : 0u;
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const int j0 = t_sub0 + 16 * c + 4 * lg - P;          // tree slot of element i = 0
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int j = j0 + i;
-                    const int wi = (j >> 5) & 3;
-                    const unsigned word = wi == 0 ? w0 : (wi == 1 ? w1 : (wi == 2 ? w2 : w3));
-                    const bool bit = (word >> (j & 31)) & 1u;
-                    const bool valid = (j < 0) | ((j < n) & bit);
-                    s[rb][c][i] = valid ? s[rb][c][i] : -INFINITY;
-                }
-            }
-        }
-        float mx = fmaxf(fmaxf(fmaxf(s[rb][0][0], s[rb][0][1]), fmaxf(s[rb][0][2], s[rb][0][3])),
-                         fmaxf(fmaxf(s[rb][1][0], s[rb][1][1]), fmaxf(s[rb][1][2], s[rb][1][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // lazy running max: all four lane groups of a row see the same mx and m_run
-        const bool grow = mx > m_run[rb] + lazy_raw;      // also true on the first finite tile
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {      // wavefront-uniform branch
-            const float m_new = grow ? mx : m_run[rb];
-            float a = grow ? __builtin_amdgcn_exp2f((m_run[rb] - m_new) * c_log2) : 1.0f;
-            if (m_run[rb] == -INFINITY) a = 0.0f;
-            l_run[rb] *= a;
-#pragma unroll
-            for (int db = 0; db < 8; ++db) o[rb][db] *= a;
-            m_run[rb] = m_new;
-        }
-        const float mref = (m_run[rb] == -INFINITY) ? 0.0f : m_run[rb];
-        const float neg = -mref * c_log2;
-        float lsum = 0.f;
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[rb][c][i], c_log2, neg));
-                lsum += e;
-                pb[rb][4 * c + i] = static_cast<__bf16>(e);
-            }
-        l_run[rb] += lsum;
-    }
-
-    // ---- O^T += V^T P^T ; V^T operand through the LDS transpose read
-#pragma unroll
-    for (int db = 0; db < 8; ++db) {
-        bf16x8 va;
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int row = 16 * c + 4 * lg + (l16 >> 2);
-            const int seg = db ^ (row & 7);
-            const unsigned char* ptr = Vs + row * AT_ROW_BYTES + seg * 32 + 8 * (l16 & 3);
-            const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (short4_t __attribute__((address_space(3)))*)(ptr));
-            const bf16x4 rb4 = __builtin_bit_cast(bf16x4, r);
-            va[4 * c + 0] = rb4[0];
-            va[4 * c + 1] = rb4[1];
-            va[4 * c + 2] = rb4[2];
-            va[4 * c + 3] = rb4[3];
-        }
-#pragma unroll
-        for (int rb = 0; rb < MB; ++rb)
-            o[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[rb], o[rb][db], 0, 0, 0);
-    }
-}
-
 struct SplitRange { int st0, st1, P, n, total; };
 
 constexpr int AT_MAX_SPLIT_PAGES = 4096;          // block-table entries of one split kept in LDS
-constexpr int AT_NBUF = 4;                         // LDS stage buffers: 3 stages in flight + 1 in use
+constexpr int AT_NBUF = 4;                         // LDS stage buffers
 constexpr int AT_STAGE_BYTES = 2 * AT_STAGE * AT_ROW_BYTES;   // K rows then V rows
-constexpr int AT_LOADS_PER_STAGE = 4;              // global->LDS instructions per wavefront per stage
+constexpr int AT_LOADS_PER_STAGE = 8;              // global->LDS instructions per wavefront per stage
 
 // Global -> LDS without passing through registers: each lane's 16 bytes land at
 // (wavefront-uniform LDS base) + lane * 16, so the swizzled LDS layout is produced by
-// choosing which global chunk each lane fetches.  One wavefront moves 4 token rows
-// (1 KB) of K or of V per instruction; 8 wavefronts x 2 x (K,V) = one 64-token stage.
-// The block-table entries of the split were copied to LDS (Tb) up front, so the lookup is
-// an LDS read and nothing but the transfers themselves occupies the vector memory counter.
+// choosing which global chunk each lane fetches.  One instruction moves 4 token rows (1 KB)
+// of K or of V; 4 wavefronts x 4 x (K,V) = one 64-token stage.
 //
 // The transfer is issued through inline assembly on purpose: the kernel keeps several stages
 // in flight and waits for them with explicit s_waitcnt vmcnt(N); transfers the compiler knows
@@ -223,31 +118,8 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
         (const __attribute__((address_space(3))) unsigned char*)(p)));
 }
 
-__device__ __forceinline__ void stage_loads(const AttnParams& p, const SplitRange& sr, int st, int wave_u,
-                                            int lane, const int32_t* __restrict__ Tb, int g,
-                                            unsigned char* buf) {
-    const int l16 = lane & 15;
-    const unsigned lds_base = __builtin_amdgcn_readfirstlane(lds_address(buf));
-    const int last = sr.total - 1;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int slot = 2 * wave_u + j;                         // 1 KB slot = 4 token rows
-        const int row = 4 * slot + (lane >> 4);                  // token row within the stage
-        const int pg = (st - sr.st0) * (AT_STAGE / GRAFT_PAGE_SIZE) + (slot >> 2);   // uniform, split-local
-        int t = st * AT_STAGE + row;
-        t = t < last ? t : last;                                 // rows past the end re-read the last token
-        const int64_t off = static_cast<int64_t>(Tb[pg]) * p.page_stride +
-                            static_cast<int64_t>(t & 15) * p.token_stride +
-                            static_cast<int64_t>(g) * p.head_stride;
-        const int kchunk = l16 ^ (row & 15);
-        const int vchunk = (((l16 >> 1) ^ (row & 7)) << 1) | (l16 & 1);
-        const __bf16* ksrc = static_cast<const __bf16*>(p.k) + off + kchunk * 8;
-        const __bf16* vsrc = static_cast<const __bf16*>(p.v) + off + vchunk * 8;
-        const unsigned lds = lds_base + slot * 1024;
-        load_global_to_lds_b128(ksrc, lds);
-        load_global_to_lds_b128(vsrc, lds + AT_STAGE * AT_ROW_BYTES);
-    }
-}
+// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt fields left at "no wait")
+#define GRAFT_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() would also drain the
 // vector memory counter and with it the global->LDS transfers of the stages still in flight.
@@ -257,124 +129,358 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt fields left at "no wait")
-#define GRAFT_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
+// ---- MFMA issue through inline assembly, accumulators in fixed AccVGPRs ----------------
+// With 512 registers per lane available the register allocator rotates MFMA accumulators
+// between register sets, parks them in AccVGPRs and copies them back for every vector ALU
+// use.  Here the placement is part of the design and is done by hand:
+//   O^T accumulators of row block rb, dim block db : a[32 rb + 4 db .. +3], accumulated in
+//       place and never touched by the vector ALUs inside the fast loop;
+//   Q^T operand of row block rb < QA, dim step ds   : a[32 MB + 16 rb + 4 ds .. +3];
+//   score tiles, probabilities, K/V operands        : VGPRs chosen by the compiler.
+// The compiler itself uses no AccVGPR in this kernel (VGPR-to-AccVGPR spilling is switched
+// off in the build, and the kernel must compile without spills); the asm statement in
+// reserve_acc_registers() lists the hand-managed ones as clobbered so that they are counted in
+// the kernel's register allocation.  asm volatile statements keep their relative order,
+// which also pins the MFMA sequence.
+// Hazards handled by construction: no vector ALU, LDS or memory instruction touches an MFMA
+// result within 16 instructions of the MFMA (the pipeline regions are far apart and explicit
+// s_nop guards the other places), dependent MFMAs on one accumulator are at least two
+// instructions apart, and AccVGPR writes are followed by s_nop before an MFMA reads them.
+#define GRAFT_ACC_BLOCK_0 "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47"
+#define GRAFT_ACC_BLOCK_1 "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95"
+#define GRAFT_ACC_BLOCK_2 "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", "a137", "a138", "a139", "a140", "a141", "a142", "a143"
+#define GRAFT_ACC_BLOCK_3 "a144", "a145", "a146", "a147", "a148", "a149", "a150", "a151", "a152", "a153", "a154", "a155", "a156", "a157", "a158", "a159", "a160", "a161", "a162", "a163", "a164", "a165", "a166", "a167", "a168", "a169", "a170", "a171", "a172", "a173", "a174", "a175", "a176", "a177", "a178", "a179", "a180", "a181", "a182", "a183", "a184", "a185", "a186", "a187", "a188", "a189", "a190", "a191"
+#define GRAFT_ACC_BLOCK_4 "a192", "a193", "a194", "a195", "a196", "a197", "a198", "a199", "a200", "a201", "a202", "a203", "a204", "a205", "a206", "a207", "a208", "a209", "a210", "a211", "a212", "a213", "a214", "a215", "a216", "a217", "a218", "a219", "a220", "a221", "a222", "a223", "a224", "a225", "a226", "a227", "a228", "a229", "a230", "a231", "a232", "a233", "a234", "a235", "a236", "a237", "a238", "a239"
+#define GRAFT_ACC_BLOCK_5 "a240", "a241", "a242", "a243", "a244", "a245", "a246", "a247", "a248", "a249", "a250", "a251", "a252", "a253", "a254", "a255"
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+#define GRAFT_CONST(name, ic) constexpr int name = decltype(ic)::value
+
+template <int MB> constexpr int q_in_acc() { return MB; }   // row blocks with Q^T in AccVGPRs (all, for MB <= 5)
+template <int MB> constexpr int acc_used() { return 32 * MB + 16 * q_in_acc<MB>(); }
+constexpr int o_reg(int rb, int db) { return 32 * rb + 4 * db; }
+template <int MB> constexpr int q_reg(int rb, int ds) { return 32 * MB + 16 * rb + 4 * ds; }
 
 template <int MB>
-__device__ __forceinline__ void attn_wave_main(const AttnParams& p, const SplitRange& sr, int r_base,
-                                               int split, int g, int b, unsigned char* kv0, unsigned char* kv1,
-                                               unsigned char* kv2, unsigned char* kv3,
-                                               const unsigned* __restrict__ Ms, const int32_t* __restrict__ Tb) {
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l16 = lane & 15, lg = lane >> 4;
-    constexpr int MBX = MB > 0 ? MB : 1;
+__device__ __forceinline__ void reserve_acc_registers() {
+    asm volatile("" ::: GRAFT_ACC_BLOCK_0);
+    if constexpr (acc_used<MB>() > 48) asm volatile("" ::: GRAFT_ACC_BLOCK_1);
+    if constexpr (acc_used<MB>() > 96) asm volatile("" ::: GRAFT_ACC_BLOCK_2);
+    if constexpr (acc_used<MB>() > 144) asm volatile("" ::: GRAFT_ACC_BLOCK_3);
+    if constexpr (acc_used<MB>() > 192) asm volatile("" ::: GRAFT_ACC_BLOCK_4);
+    if constexpr (acc_used<MB>() > 240) asm volatile("" ::: GRAFT_ACC_BLOCK_5);
+}
 
-    unsigned char* const bufs[AT_NBUF] = {kv0, kv1, kv2, kv3};
-    const int n_st = sr.st1 - sr.st0;
-    // pipeline prologue: the first three stages start streaming before anything else
-#pragma unroll
-    for (int k = 0; k < AT_NBUF - 1; ++k)
-        if (k < n_st) stage_loads(p, sr, sr.st0 + k, wave_u, lane, Tb, g, bufs[k]);
+template <int R> __device__ __forceinline__ void acc_set(float v) {
+    asm volatile("v_accvgpr_write_b32 a[%0], %1" : : "n"(R), "v"(v));
+}
+template <int R> __device__ __forceinline__ void acc_set_bits(unsigned v) {
+    asm volatile("v_accvgpr_write_b32 a[%0], %1" : : "n"(R), "v"(v));
+}
+template <int R> __device__ __forceinline__ float acc_get() {
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(v) : "n"(R));
+    return v;
+}
+template <int R> __device__ __forceinline__ void acc_scale(float a) {
+    float t;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]\n\ts_nop 1\n\tv_mul_f32 %0, %0, %2\n\ts_nop 1\n\tv_accvgpr_write_b32 a[%1], %0"
+                 : "=&v"(t)
+                 : "n"(R), "v"(a));
+}
+// score tile (VGPRs) = K operand (VGPRs) x Q^T operand (fixed AccVGPRs or VGPRs) [+ score tile]
+template <int QR> __device__ __forceinline__ void mfma_s_first_acc(floatx4& d, const bf16x8& ka) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, a[%2:%3], 0" : "=&v"(d) : "v"(ka), "n"(QR), "n"(QR + 3));
+}
+template <int QR> __device__ __forceinline__ void mfma_s_next_acc(floatx4& d, const bf16x8& ka) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, a[%2:%3], %0" : "+v"(d) : "v"(ka), "n"(QR), "n"(QR + 3));
+}
+__device__ __forceinline__ void mfma_s_first_vgpr(floatx4& d, const bf16x8& ka, const bf16x8& q) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(ka), "v"(q));
+}
+__device__ __forceinline__ void mfma_s_next_vgpr(floatx4& d, const bf16x8& ka, const bf16x8& q) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(ka), "v"(q));
+}
+// O^T tile (fixed AccVGPRs) += V^T operand (VGPRs) x P^T operand (VGPRs)
+template <int OR> __device__ __forceinline__ void mfma_o(const bf16x8& va, const uintx4& pb) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]" : : "n"(OR), "n"(OR + 3), "v"(va), "v"(pb));
+}
+// Two fp32 -> one packed pair of bf16 (round to nearest even), issued where it is written.
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+    unsigned r;
+    asm volatile("s_nop 0\n\tv_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+    return r;
+}
+#define GRAFT_MFMA_SETTLE() asm volatile("s_nop 15\n\ts_nop 7" ::: "memory")
 
-    // ---- Q rows of this wavefront stay in registers (B operand of S^T = K Q^T)
-    bf16x8 qreg[MBX][4];
-    floatx4 o[MBX][8];
-    float m_run[MBX], l_run[MBX];
+// What one wavefront keeps in VGPRs for its 16*MB query rows (O^T and most of Q^T are in AccVGPRs).
+template <int MB>
+struct WaveRows {
+    bf16x8 qv[MB - q_in_acc<MB>() > 0 ? MB - q_in_acc<MB>() : 1][4];   // Q^T of the row blocks not in AccVGPRs
+    float l_run[MB];        // lane-local partial row sums of the probabilities
+    float m_ref[MB];        // reference max of the row in log2 units (-inf: not set yet)
+    float mneg[MB];         // -(m_ref if set else 0): x = (q.k) * scale_log2e + mneg
+    float thr[MB];          // max(x) above this needs attention: -inf while unset, else the lazy bound
+};
+
+// LDS byte offsets of this lane's MFMA operands inside a 32-token sub-tile.
+// K group g = (c, ds): rows 16c + l16, 16-byte chunk (4ds + lg) ^ l16.
+__device__ __forceinline__ bf16x8 load_k_operand(const unsigned char* Ks, int g, int l16, int lg) {
+    const int c = g >> 2, ds = g & 3;
+    return *reinterpret_cast<const bf16x8*>(Ks + (16 * c + l16) * AT_ROW_BYTES + (((4 * ds + lg) ^ l16) * 16));
+}
+// V^T operand of dim block db through the LDS transpose read: a 16-lane group turns the
+// 4-token x 16-dim block (tokens 16c + 4lg .. +3, dims 16db .. +15) into "lane = dim, 4 tokens".
+__device__ __forceinline__ bf16x8 load_v_operand(const unsigned char* Vs, int db, int l16, int lg) {
+    bf16x8 va;
 #pragma unroll
-    for (int rb = 0; rb < MB; ++rb) {
-        const int r = r_base + rb * 16 + l16;
-        if (r < p.R) {
-            const int i = r / p.G, hl = r - i * p.G;
-            const __bf16* qp = static_cast<const __bf16*>(p.q) +
-                ((static_cast<size_t>(b) * p.K_max + i) * p.Hq + (g * p.G + hl)) * AT_D + lg * 8;
-#pragma unroll
-            for (int ds = 0; ds < 4; ++ds) qreg[rb][ds] = *reinterpret_cast<const bf16x8*>(qp + 32 * ds);
-        } else {
-#pragma unroll
-            for (int ds = 0; ds < 4; ++ds)
-#pragma unroll
-                for (int t = 0; t < 8; ++t) qreg[rb][ds][t] = static_cast<__bf16>(0.0f);
-        }
-        m_run[rb] = -INFINITY;
-        l_run[rb] = 0.f;
-#pragma unroll
-        for (int db = 0; db < 8; ++db) o[rb][db] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < 2; ++c) {
+        const int row = 16 * c + 4 * lg + (l16 >> 2);
+        const int seg = db ^ (row & 7);
+        const unsigned char* ptr = Vs + row * AT_ROW_BYTES + seg * 32 + 8 * (l16 & 3);
+        const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (short4_t __attribute__((address_space(3)))*)(ptr));
+        const bf16x4 r4 = __builtin_bit_cast(bf16x4, r);
+        va[4 * c + 0] = r4[0];
+        va[4 * c + 1] = r4[1];
+        va[4 * c + 2] = r4[2];
+        va[4 * c + 3] = r4[3];
     }
+    return va;
+}
 
-    // Q must have landed before the loop: a pending compiler-tracked load would make every
-    // iteration drain the vector memory counter (and the stages in flight with it).
-    GRAFT_WAIT_VMCNT(0);
-    const float c_log2 = p.scale_log2e;
-    const float lazy_raw = AT_LAZY_LOG2 / c_log2;
-
-    // ---- software pipeline over 64-token stages: stage k lives in buffer k % 4, loads run
-    //      three stages ahead; before a stage is used every wavefront waits for its own
-    //      loads of that stage (the younger stages' loads stay in flight) and meets the
-    //      others at one barrier, which also frees the buffer consumed one stage earlier.
-    for (int base = 0; base < n_st; base += AT_NBUF) {
-#pragma unroll
-        for (int i = 0; i < AT_NBUF; ++i) {
-            const int idx = base + i;
-            if (idx >= n_st) break;
-            const int younger = n_st - 1 - idx;                  // stages already issued after this one
-            if (younger >= 2) GRAFT_WAIT_VMCNT(2 * AT_LOADS_PER_STAGE);
-            else if (younger == 1) GRAFT_WAIT_VMCNT(AT_LOADS_PER_STAGE);
-            else GRAFT_WAIT_VMCNT(0);
-            lds_barrier();
-            if (idx + AT_NBUF - 1 < n_st)
-                stage_loads(p, sr, sr.st0 + idx + AT_NBUF - 1, wave_u, lane, Tb, g,
-                            bufs[(i + AT_NBUF - 1) % AT_NBUF]);
-            if (MB > 0) {
-                const int st = sr.st0 + idx;
-#pragma unroll 1
-                for (int sub = 0; sub < 2; ++sub) {
-                    const int t_sub0 = st * AT_STAGE + sub * AT_SUB;
-                    if (t_sub0 < sr.total)
-                        attn_subtile<MBX>(bufs[i] + sub * AT_SUB * AT_ROW_BYTES,
-                                          bufs[i] + AT_STAGE * AT_ROW_BYTES + sub * AT_SUB * AT_ROW_BYTES, qreg, o,
-                                          m_run, l_run, c_log2, lazy_raw, lane, t_sub0 + AT_SUB > sr.P, t_sub0,
-                                          sr.P, sr.n, r_base, p.R, p.G, Ms);
-                }
-            }
-        }
-    }
-
-    // ---- partial results: unnormalised O, running max (log2 units), running sum
-    const size_t part = ((static_cast<size_t>(b) * p.Hkv + g) * p.n_splits + split) * p.R_pad;
-#pragma unroll
-    for (int rb = 0; rb < MB; ++rb) {
-        const int r = r_base + rb * 16 + l16;
-        float l = l_run[rb];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        float* op = p.ws_o + (part + r) * AT_D + 4 * lg;
-#pragma unroll
-        for (int db = 0; db < 8; ++db)       // o[rb][db][i] = O[r][16 db + 4 lg + i]
-            *reinterpret_cast<floatx4*>(op + 16 * db) = o[rb][db];
-        if (lg == 0) {
-            float* ml = p.ws_ml + (part + r) * 2;
-            ml[0] = m_run[rb] == -INFINITY ? -INFINITY : m_run[rb] * c_log2;
-            ml[1] = l;
-        }
+// One QK^T MFMA: score tile (rb, c) accumulates dim step ds.
+template <int MB, int RB, int DS>
+__device__ __forceinline__ void qk_mfma(floatx4& acc, const bf16x8& ka, const WaveRows<MB>& w) {
+    if constexpr (RB < q_in_acc<MB>()) {
+        if constexpr (DS == 0) mfma_s_first_acc<q_reg<MB>(RB, 0)>(acc, ka);
+        else mfma_s_next_acc<q_reg<MB>(RB, DS)>(acc, ka);
+    } else {
+        if constexpr (DS == 0) mfma_s_first_vgpr(acc, ka, w.qv[RB - q_in_acc<MB>()][0]);
+        else mfma_s_next_vgpr(acc, ka, w.qv[RB - q_in_acc<MB>()][DS]);
     }
 }
 
-// Wavefronts 0..3 own MBA row blocks each, wavefronts 4..7 own MBB (<= MBA): with the
-// usual round-robin placement every SIMD hosts one wavefront of each kind, so a row
-// count like 320 = 16 * (4*3 + 4*2) is balanced over the four SIMDs.
-template <int MBA, int MBB>
+// Pipeline region 1: the matrix cores compute the raw scores of the NEXT sub-tile
+// (S^T = K Q^T into xr) while the vector ALUs turn the CURRENT sub-tile's exponents xe into
+// probabilities (pb, packed bf16) and add them to the row sums.  One MFMA and one score
+// element per slot; sched_barrier pins the interleaving because the wavefront issues in order.
+template <int MB>
+__device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ Ks, WaveRows<MB>& w,
+                                              floatx4 (&xr)[MB][2], const floatx4 (&xe)[MB][2],
+                                              uintx4 (&pb)[MB], int lane) {
+    const int l16 = lane & 15, lg = lane >> 4;
+    bf16x8 ka[3];
+    float pprev[MB];
+    ka[0] = load_k_operand(Ks, 0, l16, lg);
+    ka[1] = load_k_operand(Ks, 1, l16, lg);
+    static_for<0, 8>([&](auto g_) {
+        GRAFT_CONST(g, g_);
+        constexpr int c = g >> 2, ds = g & 3;
+        if constexpr (g + 2 < 8) ka[(g + 2) % 3] = load_k_operand(Ks, g + 2, l16, lg);
+        static_for<0, MB>([&](auto rb_) {
+            GRAFT_CONST(rb, rb_);
+            qk_mfma<MB, rb, ds>(xr[rb][c], ka[g % 3], w);
+            const float pe = __builtin_amdgcn_exp2f(xe[rb][c][ds]);
+            w.l_run[rb] += pe;
+            if constexpr (g & 1) pb[rb][g >> 1] = pack_bf16(pprev[rb], pe);
+            else pprev[rb] = pe;
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    });
+}
+
+// Pipeline region 2: the matrix cores run O^T += V^T P^T of the CURRENT sub-tile while the
+// vector ALUs turn the NEXT sub-tile's raw scores xr into exponents xe = s * scale_log2e + mneg
+// and track their lane-local maxima.  Returns whether any lane saw an exponent above its
+// row's threshold (wavefront-uniform).
+template <int MB>
+__device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ Vs, WaveRows<MB>& w,
+                                              const uintx4 (&pb)[MB], const floatx4 (&xr)[MB][2],
+                                              floatx4 (&xe)[MB][2], float c_log2, float (&lm)[MB], int lane) {
+    const int l16 = lane & 15, lg = lane >> 4;
+    bf16x8 va[3];
+    va[0] = load_v_operand(Vs, 0, l16, lg);
+    va[1] = load_v_operand(Vs, 1, l16, lg);
+    static_for<0, 8>([&](auto db_) {
+        GRAFT_CONST(db, db_);
+        if constexpr (db + 2 < 8) va[(db + 2) % 3] = load_v_operand(Vs, db + 2, l16, lg);
+        static_for<0, MB>([&](auto rb_) {
+            GRAFT_CONST(rb, rb_);
+            mfma_o<o_reg(rb, db)>(va[db % 3], pb[rb]);
+            const float x = __builtin_fmaf(xr[rb][db >> 2][db & 3], c_log2, w.mneg[rb]);
+            xe[rb][db >> 2][db & 3] = x;
+            lm[rb] = db == 0 ? x : __builtin_fmaxf(lm[rb], x);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    });
+    bool grow = false;
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) grow = grow || (lm[rb] > w.thr[rb]);
+    return __builtin_amdgcn_ballot_w64(grow) != 0;
+}
+
+// Ancestor masking of an exponent tile that reaches past the prefix (tree slots and the
+// tail): masked entries become -inf; the lane-local maxima are recomputed.
+template <int MB>
+__device__ __forceinline__ bool apply_tree_mask(floatx4 (&x)[MB][2], const WaveRows<MB>& w, float (&lm)[MB],
+                                                int lane, int t_sub0, int P, int n, int r_base, int R, int G,
+                                                const unsigned* __restrict__ Ms) {
+    const int l16 = lane & 15, lg = lane >> 4;
+    bool grow = false;
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) {
+        const int r = r_base + rb * 16 + l16;
+        const int node = r / G;
+        const bool live = r < R && node < n;
+        const int nd = live ? node : 0;
+        unsigned wd[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) wd[k] = live ? Ms[4 * nd + k] : 0u;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int j0 = t_sub0 + 16 * c + 4 * lg - P;      // tree slot of element i = 0
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = j0 + i;
+                const int wi = (j >> 5) & 3;
+                const unsigned word = wi == 0 ? wd[0] : (wi == 1 ? wd[1] : (wi == 2 ? wd[2] : wd[3]));
+                const bool bit = (word >> (j & 31)) & 1u;
+                const bool valid = (j < 0) | ((j < n) & bit);
+                x[rb][c][i] = valid ? x[rb][c][i] : -INFINITY;
+                mx = fmaxf(mx, x[rb][c][i]);
+            }
+        }
+        lm[rb] = mx;
+        grow = grow || (mx > w.thr[rb]);
+    }
+    return __builtin_amdgcn_ballot_w64(grow) != 0;
+}
+
+// Some lane saw an exponent above its row's threshold.  Rows without a reference take the
+// tile's row maximum as their reference: nothing has been accumulated for them yet, so only
+// the pending exponents are re-based.  Returns true when a row that already has a reference
+// exceeded the lazy bound: the caller then leaves the fast loop (that needs a rescale of O).
+template <int MB>
+__device__ __forceinline__ bool set_references(float (&lm)[MB], WaveRows<MB>& w, floatx4 (&x)[MB][2]) {
+    bool raise = false;
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) {
+        float mx = lm[rb];
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        lm[rb] = mx;                                      // now the row maximum, same in the row's 4 lanes
+        const bool unset = w.m_ref[rb] == -INFINITY;
+        raise = raise || (!unset && mx > w.thr[rb]);
+    }
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) return true;
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) {
+        if (w.m_ref[rb] == -INFINITY && lm[rb] > -INFINITY) {
+            w.m_ref[rb] = lm[rb];
+            w.mneg[rb] = -lm[rb];
+            w.thr[rb] = AT_LAZY_LOG2;
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[rb][c][i] -= lm[rb];
+        }
+    }
+    return false;
+}
+
+// Slow path (exact running max, classic online softmax): raise every row's reference to
+// the maximum seen so far, rescaling O and the row sums.  lm holds the row maxima of x.
+template <int MB>
+__device__ __forceinline__ void raise_references(const float (&lm)[MB], WaveRows<MB>& w, floatx4 (&x)[MB][2]) {
+    GRAFT_MFMA_SETTLE();
+    static_for<0, MB>([&](auto rb_) {
+        GRAFT_CONST(rb, rb_);
+        const float mx = lm[rb];
+        const bool unset = w.m_ref[rb] == -INFINITY;
+        const bool move = (!unset && mx > 0.0f) || (unset && mx > -INFINITY);
+        if (__builtin_amdgcn_ballot_w64(move) != 0) {
+            // rows that do not move get a = 1 and a zero shift
+            const float shift = move ? mx : 0.0f;
+            const float a = move ? (unset ? 0.0f : __builtin_amdgcn_exp2f(-mx)) : 1.0f;
+            if (move) {
+                w.m_ref[rb] = (unset ? 0.0f : w.m_ref[rb]) + mx;
+                w.mneg[rb] = -w.m_ref[rb];
+                w.thr[rb] = AT_LAZY_LOG2;
+            }
+            w.l_run[rb] *= a;
+            static_for<0, 32>([&](auto k_) {
+                GRAFT_CONST(k, k_);
+                acc_scale<32 * rb + k>(a);
+            });
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[rb][c][i] -= shift;
+        }
+    });
+    GRAFT_MFMA_SETTLE();
+}
+
+// Slow-path building blocks: the same arithmetic as the pipeline regions, one thing at a time.
+template <int MB>
+__device__ __forceinline__ void qk_only(const unsigned char* __restrict__ Ks, const WaveRows<MB>& w,
+                                        floatx4 (&xr)[MB][2], int lane) {
+    const int l16 = lane & 15, lg = lane >> 4;
+    static_for<0, 8>([&](auto g_) {
+        GRAFT_CONST(g, g_);
+        const bf16x8 ka = load_k_operand(Ks, g, l16, lg);
+        static_for<0, MB>([&](auto rb_) {
+            GRAFT_CONST(rb, rb_);
+            qk_mfma<MB, rb, (g & 3)>(xr[rb][g >> 2], ka, w);
+            asm volatile("s_nop 7" ::: "memory");
+        });
+    });
+    GRAFT_MFMA_SETTLE();
+}
+template <int MB>
+__device__ __forceinline__ void exp_only(const floatx4 (&xe)[MB][2], WaveRows<MB>& w, uintx4 (&pb)[MB]) {
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(xe[rb][e >> 2][e & 3]);
+            const float p1 = __builtin_amdgcn_exp2f(xe[rb][e >> 2][(e & 3) + 1]);
+            w.l_run[rb] += p0 + p1;
+            pb[rb][e >> 1] = pack_bf16(p0, p1);
+        }
+}
+template <int MB>
+__device__ __forceinline__ void pv_only(const unsigned char* __restrict__ Vs, const uintx4 (&pb)[MB], int lane) {
+    const int l16 = lane & 15, lg = lane >> 4;
+    static_for<0, 8>([&](auto db_) {
+        GRAFT_CONST(db, db_);
+        const bf16x8 va = load_v_operand(Vs, db, l16, lg);
+        static_for<0, MB>([&](auto rb_) {
+            GRAFT_CONST(rb, rb_);
+            mfma_o<o_reg(rb, db)>(va, pb[rb]);
+        });
+    });
+    GRAFT_MFMA_SETTLE();
+}
+
+template <int MB>
 __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p) {
-    // Four separate arrays on purpose: the compiler tracks pending global->LDS transfers per
-    // LDS variable, so reads of one stage buffer do not wait for transfers into the others.
-    __shared__ __attribute__((aligned(1024))) unsigned char kv0[AT_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char kv1[AT_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char kv2[AT_STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char kv3[AT_STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char kv[AT_NBUF][AT_STAGE_BYTES];
     __shared__ unsigned Ms[GRAFT_MAX_NODES * GRAFT_MASK_WORDS * 2];   // ancestor masks as 32-bit words
     __shared__ int32_t Tb[AT_MAX_SPLIT_PAGES];                         // this split's block-table entries
 
-    const int tid = threadIdx.x, wave = tid >> 6;
+    reserve_acc_registers<MB>();
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, lg = lane >> 4;
     const int split = blockIdx.x % p.n_splits, rt = blockIdx.x / p.n_splits;
     const int g = blockIdx.y, b = blockIdx.z;
 
@@ -392,13 +498,17 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     sr.st0 = split * spt;
     sr.st1 = (sr.st0 + spt) < n_stages ? (sr.st0 + spt) : n_stages;
     if (sr.st1 < sr.st0) sr.st1 = sr.st0;
+    const int n_st = sr.st1 - sr.st0;
 
-    if (tid < p.K_max * GRAFT_MASK_WORDS * 2)
-        Ms[tid] = reinterpret_cast<const unsigned*>(p.mask)[static_cast<size_t>(b) * p.K_max * GRAFT_MASK_WORDS * 2 + tid];
+    // the first pipeline step multiplies zero probabilities with whatever buffer 3 holds: make it zeros
+    for (int k = tid; k < AT_STAGE * AT_ROW_BYTES / 16; k += AT_THREADS)
+        reinterpret_cast<uint4*>(&kv[AT_NBUF - 1][AT_STAGE * AT_ROW_BYTES])[k] = uint4{0u, 0u, 0u, 0u};
+    for (int k = tid; k < p.K_max * GRAFT_MASK_WORDS * 2; k += AT_THREADS)
+        Ms[k] = reinterpret_cast<const unsigned*>(p.mask)[static_cast<size_t>(b) * p.K_max * GRAFT_MASK_WORDS * 2 + k];
     {
         const int32_t* table = p.block_table + static_cast<size_t>(b) * p.max_pages;
         const int first_pg = sr.st0 * (AT_STAGE / GRAFT_PAGE_SIZE);
-        const int n_pg = (sr.st1 - sr.st0) * (AT_STAGE / GRAFT_PAGE_SIZE);
+        const int n_pg = n_st * (AT_STAGE / GRAFT_PAGE_SIZE);
         const int last_pg = (sr.total - 1) >> 4;
         for (int k = tid; k < n_pg; k += AT_THREADS) {
             const int pg = first_pg + k;
@@ -407,13 +517,177 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     }
     __syncthreads();
 
-    const int tile_base = rt * (AT_WAVES / 2) * 16 * (MBA + MBB);
-    if (wave < AT_WAVES / 2) {
-        attn_wave_main<MBA>(p, sr, tile_base + wave * 16 * MBA, split, g, b, kv0, kv1, kv2, kv3, Ms, Tb);
-    } else {
-        attn_wave_main<MBB>(p, sr, tile_base + (AT_WAVES / 2) * 16 * MBA + (wave - AT_WAVES / 2) * 16 * MBB,
-                            split, g, b, kv0, kv1, kv2, kv3, Ms, Tb);
+    // ---- stage pipeline: stage k (split-local) lives in kv[k & 3]; its loads are issued two
+    //      stages ahead.  advance(k) = wait for this wavefront's loads of stage k (the next
+    //      stage's stay in flight), meet the others, then start stage k + 2.
+    const unsigned kv_base = __builtin_amdgcn_readfirstlane(lds_address(&kv[0][0]));
+    const int last_tok = sr.total - 1;
+    auto issue_stage = [&](int k) {
+        const unsigned buf = kv_base + (k & (AT_NBUF - 1)) * AT_STAGE_BYTES;
+        const int st = sr.st0 + k;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int slot = 4 * wave_u + j;                         // 1 KB slot = 4 token rows
+            const int row = 4 * slot + lg;                           // token row within the stage
+            int t = st * AT_STAGE + row;
+            t = t < last_tok ? t : last_tok;                         // rows past the end re-read the last token
+            const int64_t off = static_cast<int64_t>(Tb[k * 4 + (slot >> 2)]) * p.page_stride +
+                                static_cast<int64_t>(t & 15) * p.token_stride +
+                                static_cast<int64_t>(g) * p.head_stride;
+            const int kchunk = l16 ^ (row & 15);
+            const int vchunk = (((l16 >> 1) ^ (row & 7)) << 1) | (l16 & 1);
+            load_global_to_lds_b128(static_cast<const __bf16*>(p.k) + off + kchunk * 8, buf + slot * 1024);
+            load_global_to_lds_b128(static_cast<const __bf16*>(p.v) + off + vchunk * 8,
+                                    buf + AT_STAGE * AT_ROW_BYTES + slot * 1024);
+        }
+    };
+    auto advance = [&](int k) {
+        if (k + 1 < n_st) GRAFT_WAIT_VMCNT(AT_LOADS_PER_STAGE);
+        else GRAFT_WAIT_VMCNT(0);
+        lds_barrier();
+        if (k + 2 < n_st) issue_stage(k + 2);
+    };
+    if (n_st > 0) issue_stage(0);
+    if (n_st > 1) issue_stage(1);
+
+    // ---- this wavefront's rows: Q^T into its registers, O^T accumulators to zero
+    const int r_base = rt * (AT_WAVES * 16 * MB) + wave_u * (16 * MB);
+    WaveRows<MB> w;
+    static_for<0, MB>([&](auto rb_) {
+        GRAFT_CONST(rb, rb_);
+        const int r = r_base + rb * 16 + l16;
+        uintx4 qd[4];
+        if (r < p.R) {
+            const int i = r / p.G, hl = r - i * p.G;
+            const __bf16* qp = static_cast<const __bf16*>(p.q) +
+                ((static_cast<size_t>(b) * p.K_max + i) * p.Hq + (g * p.G + hl)) * AT_D + lg * 8;
+#pragma unroll
+            for (int ds = 0; ds < 4; ++ds) qd[ds] = *reinterpret_cast<const uintx4*>(qp + 32 * ds);
+        } else {
+#pragma unroll
+            for (int ds = 0; ds < 4; ++ds) qd[ds] = uintx4{0u, 0u, 0u, 0u};
+        }
+        if constexpr (rb < q_in_acc<MB>()) {
+            static_for<0, 16>([&](auto k_) {
+                GRAFT_CONST(k, k_);
+                acc_set_bits<q_reg<MB>(rb, 0) + k>(qd[k >> 2][k & 3]);
+            });
+        } else {
+#pragma unroll
+            for (int ds = 0; ds < 4; ++ds) w.qv[rb - q_in_acc<MB>()][ds] = __builtin_bit_cast(bf16x8, qd[ds]);
+        }
+        w.m_ref[rb] = -INFINITY;
+        w.mneg[rb] = 0.0f;
+        w.thr[rb] = -INFINITY;
+        w.l_run[rb] = 0.0f;
+        static_for<0, 32>([&](auto k_) {
+            GRAFT_CONST(k, k_);
+            acc_set<32 * rb + k>(0.0f);
+        });
+    });
+    // Q must have landed before the loop: a pending compiler-tracked load would make every
+    // iteration drain the vector memory counter (and the stages in flight with it).
+    GRAFT_WAIT_VMCNT(0);
+    GRAFT_MFMA_SETTLE();
+
+    const float c_log2 = p.scale_log2e;
+    constexpr int K_OFF = 0, V_OFF = AT_STAGE * AT_ROW_BYTES, SUB = AT_SUB * AT_ROW_BYTES;
+
+    // ---- fast loop, software pipelined over 32-token sub-tiles.  Step j: region 1 computes
+    //      the raw scores of sub-tile j (xr) while exponentiating sub-tile j-1 (xe -> pb);
+    //      region 2 accumulates P.V of sub-tile j-1 while turning xr into the exponents xe of
+    //      sub-tile j.  The first step exponentiates -inf (zero probabilities against the
+    //      zero-filled buffer 3), the last (drain) step computes scores nobody uses.  A row's
+    //      reference is the row maximum of the first tile that gives it a finite score and is
+    //      kept while later exponents stay below 2^AT_LAZY_LOG2; otherwise the wavefront leaves
+    //      for the slow loop below (exact running max, rescaling O with the vector ALUs).
+    floatx4 xr[MB][2], xe[MB][2];
+    uintx4 pb[MB];
+    float lm[MB];
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) xe[rb][c] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+
+    const int n_sub = 2 * n_st;
+    int j = 0;
+    bool slow = false;
+    for (; j <= n_sub; ++j) {
+        const bool live = j < n_sub;
+        if (live && (j & 1) == 0) advance(j >> 1);
+        const unsigned char* cur = kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB;
+        const unsigned char* prev = kv[((j - 1) >> 1) & (AT_NBUF - 1)] + ((j - 1) & 1) * SUB;
+        region_qk_exp<MB>(cur + K_OFF, w, xr, xe, pb, lane);
+        bool grow = region_pv_max<MB>(prev + V_OFF, w, pb, xr, xe, c_log2, lm, lane);
+        if (!live) break;
+        const int t_sub0 = sr.st0 * AT_STAGE + j * AT_SUB;
+        if (t_sub0 + AT_SUB > sr.P)
+            grow = apply_tree_mask<MB>(xe, w, lm, lane, t_sub0, sr.P, sr.n, r_base, p.R, p.G, Ms);
+        if (grow && set_references<MB>(lm, w, xe)) { slow = true; break; }
     }
+
+    // ---- slow loop (rare): xe holds the exponents of sub-tile j against the old references and
+    //      lm their row maxima.  One sub-tile at a time, exact running max.
+    if (slow) {
+        while (true) {
+            const unsigned char* cur = kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB;
+            raise_references<MB>(lm, w, xe);
+            exp_only<MB>(xe, w, pb);
+            pv_only<MB>(cur + V_OFF, pb, lane);
+            ++j;
+            if (j >= n_sub) break;
+            if ((j & 1) == 0) advance(j >> 1);
+            qk_only<MB>(kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB + K_OFF, w, xr, lane);
+#pragma unroll
+            for (int rb = 0; rb < MB; ++rb) {
+                float mx = -INFINITY;
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        xe[rb][c][i] = __builtin_fmaf(xr[rb][c][i], c_log2, w.mneg[rb]);
+                        mx = fmaxf(mx, xe[rb][c][i]);
+                    }
+                lm[rb] = mx;
+            }
+            const int t_sub0 = sr.st0 * AT_STAGE + j * AT_SUB;
+            if (t_sub0 + AT_SUB > sr.P)
+                apply_tree_mask<MB>(xe, w, lm, lane, t_sub0, sr.P, sr.n, r_base, p.R, p.G, Ms);
+#pragma unroll
+            for (int rb = 0; rb < MB; ++rb) {
+                float mx = lm[rb];
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                lm[rb] = mx;
+            }
+        }
+    }
+    GRAFT_MFMA_SETTLE();
+
+    // ---- partial results: unnormalised O, reference max (log2 units), row sum
+    const size_t part = ((static_cast<size_t>(b) * p.Hkv + g) * p.n_splits + split) * p.R_pad;
+    static_for<0, MB>([&](auto rb_) {
+        GRAFT_CONST(rb, rb_);
+        const int r = r_base + rb * 16 + l16;
+        float l = w.l_run[rb];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        float* op = p.ws_o + (part + r) * AT_D + 4 * lg;
+        static_for<0, 8>([&](auto db_) {
+            GRAFT_CONST(db, db_);
+            floatx4 t;
+            t[0] = acc_get<o_reg(rb, db) + 0>();
+            t[1] = acc_get<o_reg(rb, db) + 1>();
+            t[2] = acc_get<o_reg(rb, db) + 2>();
+            t[3] = acc_get<o_reg(rb, db) + 3>();
+            *reinterpret_cast<floatx4*>(op + 16 * db) = t;
+        });
+        if (lg == 0) {
+            float* ml = p.ws_ml + (part + r) * 2;
+            ml[0] = w.m_ref[rb];
+            ml[1] = l;
+        }
+    });
 }
 
 // Merge the splits of one output row: out = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
@@ -573,7 +847,7 @@ __global__ __launch_bounds__(SM_THREADS) void tree_attn_simple_kernel(AttnParams
 // ---------------------------------------------------------------------------
 struct AttnPlan {
     bool mfma;
-    int mba, mbb, n_row_tiles, n_splits, r_pad;
+    int mb, n_row_tiles, n_splits, r_pad;
     size_t ws_o_bytes, ws_bytes;
 };
 
@@ -583,13 +857,10 @@ static AttnPlan make_plan(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
     pl.mfma = (dtype == GRAFT_BF16 && D == AT_D);
     if (!pl.mfma) return pl;
     const int R = K_max * (Hq / Hkv);
-    const int blocks = (R + 15) / 16;                            // 16-row MFMA blocks
-    pl.n_row_tiles = (blocks + AT_MAX_BLOCKS - 1) / AT_MAX_BLOCKS;
-    const int per_tile = (blocks + pl.n_row_tiles - 1) / pl.n_row_tiles;
-    const int per_simd = (per_tile + 3) / 4;                     // blocks per SIMD = MBA + MBB
-    pl.mba = (per_simd + 1) / 2;
-    pl.mbb = per_simd / 2;
-    pl.r_pad = pl.n_row_tiles * 64 * (pl.mba + pl.mbb);
+    const int rows_per_mb = AT_WAVES * 16;                       // rows a workgroup covers per MB
+    pl.n_row_tiles = (R + rows_per_mb * AT_MAX_MB - 1) / (rows_per_mb * AT_MAX_MB);
+    pl.mb = (R + pl.n_row_tiles * rows_per_mb - 1) / (pl.n_row_tiles * rows_per_mb);
+    pl.r_pad = pl.n_row_tiles * pl.mb * rows_per_mb;
     const int stages = (max_pages * GRAFT_PAGE_SIZE + AT_STAGE - 1) / AT_STAGE;
     const int units = B * Hkv * pl.n_row_tiles;
     int splits = (256 + units - 1) / units;                      // one workgroup per CU
@@ -623,9 +894,9 @@ static void prof_record(bool start, hipStream_t s) {
     }
 }
 
-template <int MBA, int MBB>
+template <int MB>
 static void launch_mfma(const AttnParams& p, dim3 grid, hipStream_t s) {
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<MBA, MBB>), grid, dim3(AT_THREADS), 0, s, p);
+    hipLaunchKernelGGL(tree_attn_mfma_kernel<MB>, grid, dim3(AT_THREADS), 0, s, p);
 }
 
 }  // namespace graft
@@ -693,13 +964,12 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     p.ws_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + pl.ws_o_bytes);
     dim3 grid(pl.n_splits * pl.n_row_tiles, Hkv, B);
     prof_record(true, s);
-    switch (pl.mba * 4 + pl.mbb) {
-        case 1 * 4 + 0: launch_mfma<1, 0>(p, grid, s); break;
-        case 1 * 4 + 1: launch_mfma<1, 1>(p, grid, s); break;
-        case 2 * 4 + 1: launch_mfma<2, 1>(p, grid, s); break;
-        case 2 * 4 + 2: launch_mfma<2, 2>(p, grid, s); break;
-        case 3 * 4 + 2: launch_mfma<3, 2>(p, grid, s); break;
-        default: launch_mfma<3, 3>(p, grid, s); break;
+    switch (pl.mb) {
+        case 1: launch_mfma<1>(p, grid, s); break;
+        case 2: launch_mfma<2>(p, grid, s); break;
+        case 3: launch_mfma<3>(p, grid, s); break;
+        case 4: launch_mfma<4>(p, grid, s); break;
+        default: launch_mfma<5>(p, grid, s); break;
     }
     prof_record(false, s);
     int32_t rc = check_launch();
