@@ -147,6 +147,36 @@ def test_large_scores_stay_finite():
     assert np.abs(got - ref.astype(np.float32)).max() <= 4e-2      # bf16 rounding of O(4) outputs
 
 
+def test_scores_that_outgrow_the_reference():
+    """Scores rising steadily along the sequence (by far more than the lazy bound of the fast
+    path) force the exact running-max fallback; falling scores must stay on the fast path.
+    Both must match the oracle."""
+    w = shape_workload(2, 24, 8, 2, 128, 700)
+    att = inputs.make_attention_inputs(w, seed=13)
+    pages = att["pages_per_seq"]
+    k = inputs.bf16_bits_to_f32(att["k_cache"][0]).copy()
+    q = inputs.bf16_bits_to_f32(att["q"][0]).copy()
+    for b in range(w.B):
+        for lp in range(pages):
+            t = lp * 16 + np.arange(16)
+            k[att["block_table"][b, lp]] = (t * 0.0153)[None, :, None]       # k_t = t * beta in every dim
+    q[:] = 1.0
+    q[:, :, 1::2, :] = -1.0                                                  # odd heads: falling scores
+    q[:, :, 2, :] = 0.01                                                     # one nearly flat head
+    att["k_cache"] = [inputs.f32_to_bf16_bits(k)]
+    att["q"] = [inputs.f32_to_bf16_bits(q)]
+    rng = np.random.default_rng(13)
+    parent = np.stack([inputs.random_recursive_tree(rng, w.K, 8) for _ in range(w.B)])
+    n_nodes = np.array([w.K, w.K], np.int32)
+    prefix = np.array([w.P, 333], np.int32)
+    mask = gpu_mask(parent, n_nodes, prefix)
+    got = run_attn(att, "bf16", prefix, n_nodes, mask, w.Hkv)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
+                           att["block_table"], prefix, n_nodes, parent, w.Hq, w.Hkv, w.D, 16, att["scale"])
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref.astype(np.float32)).max() <= 4e-2       # outputs are single V rows of size O(4)
+
+
 def test_c2_full_size_all_rows():
     w = inputs.get_workload("c2")
     s = inputs.make_step_inputs(w)
