@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -29,14 +30,113 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+ATTN_ASM = os.path.join(OBJ_DIR, "tree_attn-hip-amdgcn-amd-amdhsa-gfx950.s")
+
+
 def _compile(src: str, extra):
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    keep = ["-save-temps=obj"] if src == "tree_attn.hip" else []    # keeps the device assembly for the check below
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, *keep, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stdout))
     warn = [l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l and l.strip()]
     return obj, "\n".join(warn)
+
+
+def _reg_span(tok: str):
+    """'v12' -> ('v', 12, 12); 'a[4:7]' -> ('a', 4, 7); numbers may be hexadecimal; else None."""
+    m = re.fullmatch(r"([va])(\d+|0x[0-9a-f]+)", tok)
+    if m:
+        n = int(m.group(2), 0)
+        return m.group(1), n, n
+    m = re.fullmatch(r"([va])\[(\d+|0x[0-9a-f]+):(\d+|0x[0-9a-f]+)\]", tok)
+    if m:
+        return m.group(1), int(m.group(2), 0), int(m.group(3), 0)
+    return None
+
+
+def check_attention_asm(asm_text: str):
+    """Checks the generated device assembly of the MFMA attention kernels against the rules
+    their hand-placed registers and inline-assembly MFMAs rely on.  Returns a list of
+    violations (empty = fine):
+      * no scratch memory (register spills) in any of the kernels;
+      * outside the inline-assembly blocks no instruction names an AccVGPR below 48 * MB (the
+        accumulators and the Q operand live there and the compiler must not touch them);
+      * no MFMA has a vector ALU instruction writing one of its VGPR sources within the two
+        preceding wait states (an s_nop k counts k + 1): the hardware needs them and the
+        compiler does not know that the asm statement is an MFMA.
+    """
+    problems = []
+    lines = asm_text.split("\n")
+    kernel, mb, in_asm, desc = None, 0, False, ""
+    history = []          # (wait states, destination span or None) of the preceding instructions
+    for ln, raw in enumerate(lines, 1):
+        text = raw.split(";")[0].strip() if not raw.lstrip().startswith(";") else ""
+        m = re.match(r"^(_ZN5graft21tree_attn_mfma_kernelILi(\d+)E\w*):", raw)
+        if m:
+            kernel, mb, history = m.group(1), int(m.group(2)), [(1, ("v", 0, 1 << 20))]
+            continue
+        if kernel and raw.startswith(".Lfunc_end"):
+            kernel = None
+            continue
+        if "ASMSTART" in raw:
+            in_asm = True
+            continue
+        if "ASMEND" in raw:
+            in_asm = False
+            continue
+        m = re.match(r"\s*\.amdhsa_kernel\s+(\S+)", raw)
+        if m:
+            desc = m.group(1)
+            continue
+        m = re.match(r"\s*\.amdhsa_private_segment_fixed_size\s+(\d+)", raw)
+        if m:
+            if "tree_attn_mfma_kernel" in desc and int(m.group(1)) != 0:
+                problems.append("%s uses %s bytes of scratch memory (spills)" % (desc, m.group(1)))
+            continue
+        if not kernel:
+            continue
+        if raw.startswith(".LBB") or raw.startswith(".Ltmp"):
+            if raw.startswith(".LBB"):
+                # another block may jump here: assume that its last instruction wrote every VGPR
+                history = [(1, ("v", 0, 1 << 20))]
+            continue
+        if not text or text.startswith("."):
+            continue
+        parts = text.replace(",", " ").split()
+        op, args = parts[0], parts[1:]
+        if not in_asm:
+            for a in args:
+                sp = _reg_span(a)
+                if sp and sp[0] == "a" and sp[1] < 48 * mb:
+                    problems.append("line %d (%s): compiler-generated use of a hand-managed AccVGPR: %s"
+                                    % (ln, kernel, text))
+        if op.startswith("v_mfma"):
+            srcs = [sp for sp in map(_reg_span, args[1:]) if sp and sp[0] == "v"]
+            states = 0
+            for w, dst in reversed(history):
+                if states >= 2:
+                    break
+                if dst is not None and any(dst[1] <= s_[2] and s_[1] <= dst[2] for s_ in srcs):
+                    problems.append("line %d (%s): vector ALU write of an MFMA source %d wait state(s) before: %s"
+                                    % (ln, kernel, states, text))
+                    break
+                states += w
+            history.append((1, None))
+            continue
+        if op == "s_nop":
+            history.append((int(args[0], 0) + 1, None))
+            continue
+        dst = None
+        if op.startswith("v_") and not op.startswith(("v_cmp", "v_readlane", "v_readfirstlane")) and args:
+            sp = _reg_span(args[0])
+            if sp and sp[0] == "v":
+                dst = sp
+        history.append((1, dst))
+        if len(history) > 8:
+            del history[0]
+    return problems
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
@@ -48,6 +148,14 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         for _, w in results:
             if w:
                 print(w)
+    with open(ATTN_ASM) as f:
+        problems = check_attention_asm(f.read())
+    for name in os.listdir(OBJ_DIR):             # the other intermediate files are not needed
+        if name.startswith("tree_attn") and not name.endswith((".o", "gfx950.s")) or name.endswith(".hipfb"):
+            os.remove(os.path.join(OBJ_DIR, name))
+    if problems:
+        raise RuntimeError("tree_attn.hip: the generated assembly breaks a rule of the hand-scheduled kernel:\n  "
+                           + "\n  ".join(problems[:20]))
     tmp = LIB + ".tmp%d" % os.getpid()
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *[o for o, _ in results], "-o", tmp]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -113,6 +113,15 @@ __device__ __forceinline__ void load_global_to_lds_b128(const void* gptr, unsign
                  : "memory");
 }
 
+// Same with the global address given as (wavefront-uniform 64-bit base) + (32-bit byte offset
+// of the lane).
+__device__ __forceinline__ void load_global_to_lds_b128(const void* base, unsigned lane_off, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(lane_off), "s"(base)
+                 : "memory");
+}
+
 __device__ __forceinline__ unsigned lds_address(const void* p) {
     return static_cast<unsigned>(reinterpret_cast<size_t>(
         (const __attribute__((address_space(3))) unsigned char*)(p)));
@@ -140,12 +149,15 @@ __device__ __forceinline__ void lds_barrier() {
 // The compiler itself uses no AccVGPR in this kernel (VGPR-to-AccVGPR spilling is switched
 // off in the build, and the kernel must compile without spills); the asm statement in
 // reserve_acc_registers() lists the hand-managed ones as clobbered so that they are counted in
-// the kernel's register allocation.  asm volatile statements keep their relative order,
-// which also pins the MFMA sequence.
+// the kernel's register allocation; it is repeated inside the loops so that the compiler never
+// parks a value of its own in one of them across the MFMAs.  asm volatile statements keep
+// their relative order, which also pins the MFMA sequence.
 // Hazards handled by construction: no vector ALU, LDS or memory instruction touches an MFMA
 // result within 16 instructions of the MFMA (the pipeline regions are far apart and explicit
 // s_nop guards the other places), dependent MFMAs on one accumulator are at least two
-// instructions apart, and AccVGPR writes are followed by s_nop before an MFMA reads them.
+// instructions apart, AccVGPR writes are followed by s_nop before an MFMA reads them, every
+// MFMA asm begins with s_nop 1 (a vector ALU write of one of its VGPR sources may sit right
+// in front of it), and constants used as MFMA sources are made opaque to the compiler.
 #define GRAFT_ACC_BLOCK_0 "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47"
 #define GRAFT_ACC_BLOCK_1 "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95"
 #define GRAFT_ACC_BLOCK_2 "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", "a137", "a138", "a139", "a140", "a141", "a142", "a143"
@@ -194,39 +206,82 @@ template <int R> __device__ __forceinline__ void acc_scale(float a) {
                  : "=&v"(t)
                  : "n"(R), "v"(a));
 }
-// score tile (VGPRs) = K operand (VGPRs) x Q^T operand (fixed AccVGPRs or VGPRs) [+ score tile]
-template <int QR> __device__ __forceinline__ void mfma_s_first_acc(floatx4& d, const bf16x8& ka) {
-    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, a[%2:%3], 0" : "=&v"(d) : "v"(ka), "n"(QR), "n"(QR + 3));
+// The compiler does not know that these asm statements are MFMAs, so it inserts none of the
+// wait states an MFMA needs after a vector ALU write of one of its VGPR sources (2 for the
+// A and B operands, 1 for C: measured on gfx950, a shorter distance makes the MFMA read the
+// old register contents).  Two mechanisms cover this: GUARD = true puts s_nop 1 in front of
+// the MFMA (used wherever the preceding instructions are the compiler's choice and the cost
+// does not matter), and the build checks the generated assembly of this file and fails if
+// any MFMA has a vector ALU write of one of its sources within the two preceding
+// instructions.  Constants used as MFMA sources are made opaque to the compiler so that it
+// cannot rematerialise them in front of the statement.
+#define GRAFT_MFMA_GUARD "s_nop 1\n\t"
+// exponent tile (VGPRs) = K operand (VGPRs) x Q'^T operand (fixed AccVGPRs) + C, where C is the
+// tile being accumulated or, for the first dim step, the row's negated reference.
+template <int QR, bool GUARD = false>
+__device__ __forceinline__ void mfma_x_first(floatx4& d, const bf16x8& ka, const floatx4& c) {
+    if constexpr (GUARD)
+        asm volatile(GRAFT_MFMA_GUARD "v_mfma_f32_16x16x32_bf16 %0, %1, a[%2:%3], %4"
+                     : "=&v"(d) : "v"(ka), "n"(QR), "n"(QR + 3), "v"(c));
+    else
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, a[%2:%3], %4"
+                     : "=&v"(d) : "v"(ka), "n"(QR), "n"(QR + 3), "v"(c));
 }
-template <int QR> __device__ __forceinline__ void mfma_s_next_acc(floatx4& d, const bf16x8& ka) {
-    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, a[%2:%3], %0" : "+v"(d) : "v"(ka), "n"(QR), "n"(QR + 3));
-}
-__device__ __forceinline__ void mfma_s_first_vgpr(floatx4& d, const bf16x8& ka, const bf16x8& q) {
-    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(ka), "v"(q));
-}
-__device__ __forceinline__ void mfma_s_next_vgpr(floatx4& d, const bf16x8& ka, const bf16x8& q) {
-    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(ka), "v"(q));
+template <int QR, bool GUARD = false>
+__device__ __forceinline__ void mfma_x_next(floatx4& d, const bf16x8& ka) {
+    if constexpr (GUARD)
+        asm volatile(GRAFT_MFMA_GUARD "v_mfma_f32_16x16x32_bf16 %0, %1, a[%2:%3], %0"
+                     : "+v"(d) : "v"(ka), "n"(QR), "n"(QR + 3));
+    else
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, a[%2:%3], %0" : "+v"(d) : "v"(ka), "n"(QR), "n"(QR + 3));
 }
 // O^T tile (fixed AccVGPRs) += V^T operand (VGPRs) x P^T operand (VGPRs)
-template <int OR> __device__ __forceinline__ void mfma_o(const bf16x8& va, const uintx4& pb) {
-    asm volatile("v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]" : : "n"(OR), "n"(OR + 3), "v"(va), "v"(pb));
+template <int OR, bool GUARD = false>
+__device__ __forceinline__ void mfma_o(const bf16x8& va, const uintx4& pb) {
+    if constexpr (GUARD)
+        asm volatile(GRAFT_MFMA_GUARD "v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]"
+                     : : "n"(OR), "n"(OR + 3), "v"(va), "v"(pb));
+    else
+        asm volatile("v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]"
+                     : : "n"(OR), "n"(OR + 3), "v"(va), "v"(pb));
 }
-// Two fp32 -> one packed pair of bf16 (round to nearest even), issued where it is written.
+// row sums (VGPRs) += ones x P^T operand: every element of the tile ends up holding the row's sum
+template <bool GUARD = false>
+__device__ __forceinline__ void mfma_rowsum(floatx4& l, const bf16x8& ones, const uintx4& pb) {
+    if constexpr (GUARD)
+        asm volatile(GRAFT_MFMA_GUARD "v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(l) : "v"(ones), "v"(pb));
+    else
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(l) : "v"(ones), "v"(pb));
+}
+// Two fp32 -> one packed pair of bf16 (round to nearest even): v_cvt_pk_bf16_f32.
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+    typedef float floatx2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(floatx2{lo, hi}, bf16x2));
+}
+// A register holding a bit pattern the compiler cannot see through (so it is kept, not
+// rematerialised in front of an MFMA that reads it).
+__device__ __forceinline__ unsigned opaque_bits(unsigned v) {
     unsigned r;
-    asm volatile("s_nop 0\n\tv_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+    asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "s"(v));
     return r;
 }
 #define GRAFT_MFMA_SETTLE() asm volatile("s_nop 15\n\ts_nop 7" ::: "memory")
+// An empty asm that reads x: the registers of x stay allocated up to this point.  Used in the
+// slow path after a group of MFMAs so that their source registers are not reused in between.
+// (Not inside the pipeline regions: a use of an operand buffer after its reload has been
+// issued makes the compiler wait for that reload, which undoes the prefetch.)
+#define GRAFT_KEEP(x) asm volatile("" : : "v"(x))
 
-// What one wavefront keeps in VGPRs for its 16*MB query rows (O^T and most of Q^T are in AccVGPRs).
+// What one wavefront keeps in VGPRs for its 16*MB query rows (O^T and Q'^T are in AccVGPRs).
+// Exponents are in log2 units throughout: Q' = bf16(Q * scale * log2 e), so that the MFMA
+// result q'.k - m_ref is directly the argument of exp2.
 template <int MB>
 struct WaveRows {
-    bf16x8 qv[MB - q_in_acc<MB>() > 0 ? MB - q_in_acc<MB>() : 1][4];   // Q^T of the row blocks not in AccVGPRs
-    float l_run[MB];        // lane-local partial row sums of the probabilities
+    floatx4 negm[MB];       // {-m_ref} x 4: accumulator input of the first QK^T step (0 while unset)
+    floatx4 lsum[MB];       // row sums of the bf16 probabilities (all four elements equal)
     float m_ref[MB];        // reference max of the row in log2 units (-inf: not set yet)
-    float mneg[MB];         // -(m_ref if set else 0): x = (q.k) * scale_log2e + mneg
-    float thr[MB];          // max(x) above this needs attention: -inf while unset, else the lazy bound
+    float thr[MB];          // an exponent above this needs attention: -inf while unset, else the lazy bound
 };
 
 // LDS byte offsets of this lane's MFMA operands inside a 32-token sub-tile.
@@ -255,29 +310,17 @@ __device__ __forceinline__ bf16x8 load_v_operand(const unsigned char* Vs, int db
     return va;
 }
 
-// One QK^T MFMA: score tile (rb, c) accumulates dim step ds.
-template <int MB, int RB, int DS>
-__device__ __forceinline__ void qk_mfma(floatx4& acc, const bf16x8& ka, const WaveRows<MB>& w) {
-    if constexpr (RB < q_in_acc<MB>()) {
-        if constexpr (DS == 0) mfma_s_first_acc<q_reg<MB>(RB, 0)>(acc, ka);
-        else mfma_s_next_acc<q_reg<MB>(RB, DS)>(acc, ka);
-    } else {
-        if constexpr (DS == 0) mfma_s_first_vgpr(acc, ka, w.qv[RB - q_in_acc<MB>()][0]);
-        else mfma_s_next_vgpr(acc, ka, w.qv[RB - q_in_acc<MB>()][DS]);
-    }
-}
-
-// Pipeline region 1: the matrix cores compute the raw scores of the NEXT sub-tile
-// (S^T = K Q^T into xr) while the vector ALUs turn the CURRENT sub-tile's exponents xe into
-// probabilities (pb, packed bf16) and add them to the row sums.  One MFMA and one score
-// element per slot; sched_barrier pins the interleaving because the wavefront issues in order.
+// Pipeline region 1: the matrix cores compute the exponents of the NEXT sub-tile
+// (X^T = K Q'^T - m_ref into xn) while the vector ALUs turn the CURRENT sub-tile's exponents
+// xc into probabilities (pb, packed bf16).  One MFMA and one exponential per slot;
+// sched_barrier pins the interleaving because the wavefront issues in order.
 template <int MB>
-__device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ Ks, WaveRows<MB>& w,
-                                              floatx4 (&xr)[MB][2], const floatx4 (&xe)[MB][2],
+__device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ Ks, const WaveRows<MB>& w,
+                                              floatx4 (&xn)[MB][2], const floatx4 (&xc)[MB][2],
                                               uintx4 (&pb)[MB], int lane) {
     const int l16 = lane & 15, lg = lane >> 4;
     bf16x8 ka[3];
-    float pprev[MB];
+    float e0[MB], e1[MB];       // exponentials waiting to be packed (a pair is packed one group later)
     ka[0] = load_k_operand(Ks, 0, l16, lg);
     ka[1] = load_k_operand(Ks, 1, l16, lg);
     static_for<0, 8>([&](auto g_) {
@@ -286,24 +329,29 @@ __device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ 
         if constexpr (g + 2 < 8) ka[(g + 2) % 3] = load_k_operand(Ks, g + 2, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
-            qk_mfma<MB, rb, ds>(xr[rb][c], ka[g % 3], w);
-            const float pe = __builtin_amdgcn_exp2f(xe[rb][c][ds]);
-            w.l_run[rb] += pe;
-            if constexpr (g & 1) pb[rb][g >> 1] = pack_bf16(pprev[rb], pe);
-            else pprev[rb] = pe;
+            constexpr bool guard = (g == 0 && rb == 0);
+            if constexpr (ds == 0) mfma_x_first<q_reg<MB>(rb, 0), guard>(xn[rb][c], ka[g % 3], w.negm[rb]);
+            else mfma_x_next<q_reg<MB>(rb, ds), guard>(xn[rb][c], ka[g % 3]);
+            if constexpr ((g & 1) == 0 && g >= 2) pb[rb][(g - 2) >> 1] = pack_bf16(e0[rb], e1[rb]);
+            const float pe = __builtin_amdgcn_exp2f(xc[rb][c][ds]);
+            if constexpr (g & 1) e1[rb] = pe;
+            else e0[rb] = pe;
             __builtin_amdgcn_sched_barrier(0);
         });
     });
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) pb[rb][3] = pack_bf16(e0[rb], e1[rb]);
+    __builtin_amdgcn_sched_barrier(0);
 }
 
-// Pipeline region 2: the matrix cores run O^T += V^T P^T of the CURRENT sub-tile while the
-// vector ALUs turn the NEXT sub-tile's raw scores xr into exponents xe = s * scale_log2e + mneg
-// and track their lane-local maxima.  Returns whether any lane saw an exponent above its
-// row's threshold (wavefront-uniform).
+// Pipeline region 2: the matrix cores run O^T += V^T P^T and the row sums of the CURRENT
+// sub-tile while the vector ALUs scan the NEXT sub-tile's exponents for their lane-local
+// maxima.  Returns whether any lane saw an exponent above its row's threshold
+// (wavefront-uniform).
 template <int MB>
 __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ Vs, WaveRows<MB>& w,
-                                              const uintx4 (&pb)[MB], const floatx4 (&xr)[MB][2],
-                                              floatx4 (&xe)[MB][2], float c_log2, float (&lm)[MB], int lane) {
+                                              const uintx4 (&pb)[MB], const floatx4 (&xn)[MB][2],
+                                              const bf16x8& ones, float (&lm)[MB], int lane) {
     const int l16 = lane & 15, lg = lane >> 4;
     bf16x8 va[3];
     va[0] = load_v_operand(Vs, 0, l16, lg);
@@ -313,17 +361,25 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
         if constexpr (db + 2 < 8) va[(db + 2) % 3] = load_v_operand(Vs, db + 2, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
-            mfma_o<o_reg(rb, db)>(va[db % 3], pb[rb]);
-            const float x = __builtin_fmaf(xr[rb][db >> 2][db & 3], c_log2, w.mneg[rb]);
-            xe[rb][db >> 2][db & 3] = x;
-            lm[rb] = db == 0 ? x : __builtin_fmaxf(lm[rb], x);
+            mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(va[db % 3], pb[rb]);
+            if constexpr (db < 4) {          // two exponents per slot: 4 slots cover the row block's 8
+                const float a = xn[rb][db >> 1][2 * (db & 1)], b = xn[rb][db >> 1][2 * (db & 1) + 1];
+                lm[rb] = db == 0 ? __builtin_fmaxf(a, b) : __builtin_fmaxf(__builtin_fmaxf(lm[rb], a), b);
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
+    });
+    static_for<0, MB>([&](auto rb_) {
+        GRAFT_CONST(rb, rb_);
+        mfma_rowsum(w.lsum[rb], ones, pb[rb]);
     });
     bool grow = false;
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) grow = grow || (lm[rb] > w.thr[rb]);
-    return __builtin_amdgcn_ballot_w64(grow) != 0;
+    const bool any = __builtin_amdgcn_ballot_w64(grow) != 0;
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) GRAFT_KEEP(pb[rb]);
+    return any;
 }
 
 // Ancestor masking of an exponent tile that reaches past the prefix (tree slots and the
@@ -346,6 +402,7 @@ __device__ __forceinline__ bool apply_tree_mask(floatx4 (&x)[MB][2], const WaveR
         float mx = -INFINITY;
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
+            reserve_acc_registers<MB>();                      // no temporaries of the compiler's in the accumulators
             const int j0 = t_sub0 + 16 * c + 4 * lg - P;      // tree slot of element i = 0
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -385,7 +442,7 @@ __device__ __forceinline__ bool set_references(float (&lm)[MB], WaveRows<MB>& w,
     for (int rb = 0; rb < MB; ++rb) {
         if (w.m_ref[rb] == -INFINITY && lm[rb] > -INFINITY) {
             w.m_ref[rb] = lm[rb];
-            w.mneg[rb] = -lm[rb];
+            w.negm[rb] = floatx4{-lm[rb], -lm[rb], -lm[rb], -lm[rb]};
             w.thr[rb] = AT_LAZY_LOG2;
 #pragma unroll
             for (int c = 0; c < 2; ++c)
@@ -412,10 +469,10 @@ __device__ __forceinline__ void raise_references(const float (&lm)[MB], WaveRows
             const float a = move ? (unset ? 0.0f : __builtin_amdgcn_exp2f(-mx)) : 1.0f;
             if (move) {
                 w.m_ref[rb] = (unset ? 0.0f : w.m_ref[rb]) + mx;
-                w.mneg[rb] = -w.m_ref[rb];
+                w.negm[rb] = floatx4{-w.m_ref[rb], -w.m_ref[rb], -w.m_ref[rb], -w.m_ref[rb]};
                 w.thr[rb] = AT_LAZY_LOG2;
             }
-            w.l_run[rb] *= a;
+            w.lsum[rb] *= a;
             static_for<0, 32>([&](auto k_) {
                 GRAFT_CONST(k, k_);
                 acc_scale<32 * rb + k>(a);
@@ -432,43 +489,61 @@ __device__ __forceinline__ void raise_references(const float (&lm)[MB], WaveRows
 // Slow-path building blocks: the same arithmetic as the pipeline regions, one thing at a time.
 template <int MB>
 __device__ __forceinline__ void qk_only(const unsigned char* __restrict__ Ks, const WaveRows<MB>& w,
-                                        floatx4 (&xr)[MB][2], int lane) {
+                                        floatx4 (&x)[MB][2], int lane) {
     const int l16 = lane & 15, lg = lane >> 4;
     static_for<0, 8>([&](auto g_) {
         GRAFT_CONST(g, g_);
         const bf16x8 ka = load_k_operand(Ks, g, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
-            qk_mfma<MB, rb, (g & 3)>(xr[rb][g >> 2], ka, w);
+            if constexpr ((g & 3) == 0) mfma_x_first<q_reg<MB>(rb, 0), true>(x[rb][g >> 2], ka, w.negm[rb]);
+            else mfma_x_next<q_reg<MB>(rb, (g & 3)), true>(x[rb][g >> 2], ka);
             asm volatile("s_nop 7" ::: "memory");
         });
+        asm volatile("s_nop 15" ::: "memory");
+        GRAFT_KEEP(ka);
     });
     GRAFT_MFMA_SETTLE();
 }
 template <int MB>
-__device__ __forceinline__ void exp_only(const floatx4 (&xe)[MB][2], WaveRows<MB>& w, uintx4 (&pb)[MB]) {
+__device__ __forceinline__ void exp_only(const floatx4 (&x)[MB][2], uintx4 (&pb)[MB]) {
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(xe[rb][e >> 2][e & 3]);
-            const float p1 = __builtin_amdgcn_exp2f(xe[rb][e >> 2][(e & 3) + 1]);
-            w.l_run[rb] += p0 + p1;
+            const float p0 = __builtin_amdgcn_exp2f(x[rb][e >> 2][e & 3]);
+            const float p1 = __builtin_amdgcn_exp2f(x[rb][e >> 2][(e & 3) + 1]);
             pb[rb][e >> 1] = pack_bf16(p0, p1);
         }
 }
 template <int MB>
-__device__ __forceinline__ void pv_only(const unsigned char* __restrict__ Vs, const uintx4 (&pb)[MB], int lane) {
+__device__ __forceinline__ void pv_only(const unsigned char* __restrict__ Vs, WaveRows<MB>& w,
+                                        const uintx4 (&pb)[MB], const bf16x8& ones, int lane) {
     const int l16 = lane & 15, lg = lane >> 4;
     static_for<0, 8>([&](auto db_) {
         GRAFT_CONST(db, db_);
         const bf16x8 va = load_v_operand(Vs, db, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
-            mfma_o<o_reg(rb, db)>(va, pb[rb]);
+            mfma_o<o_reg(rb, db), true>(va, pb[rb]);
+            asm volatile("s_nop 7" ::: "memory");
         });
+        asm volatile("s_nop 15" ::: "memory");
+        GRAFT_KEEP(va);
+    });
+    static_for<0, MB>([&](auto rb_) {
+        GRAFT_CONST(rb, rb_);
+        mfma_rowsum<true>(w.lsum[rb], ones, pb[rb]);
+        asm volatile("s_nop 7" ::: "memory");
     });
     GRAFT_MFMA_SETTLE();
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) GRAFT_KEEP(pb[rb]);
+}
+
+// Rounds q * f to bf16 for two packed bf16 values.
+__device__ __forceinline__ unsigned scale_bf16_pair(unsigned q2, float f) {
+    return pack_bf16(__uint_as_float(q2 << 16) * f, __uint_as_float(q2 & 0xffff0000u) * f);
 }
 
 template <int MB>
@@ -483,6 +558,21 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     const int l16 = lane & 15, lg = lane >> 4;
     const int split = blockIdx.x % p.n_splits, rt = blockIdx.x / p.n_splits;
     const int g = blockIdx.y, b = blockIdx.z;
+
+    // Q rows of this wavefront: the loads are issued first so that their latency overlaps the
+    // set-up below (rows past R read row 0 and are zeroed when converted)
+    const int r_base = rt * (AT_WAVES * 16 * MB) + wave_u * (16 * MB);
+    uintx4 qd[MB][4];
+#pragma unroll
+    for (int rb = 0; rb < MB; ++rb) {
+        const int r = r_base + rb * 16 + l16;
+        const int rc = r < p.R ? r : 0;
+        const int i = rc / p.G, hl = rc - i * p.G;
+        const __bf16* qp = static_cast<const __bf16*>(p.q) +
+            ((static_cast<size_t>(b) * p.K_max + i) * p.Hq + (g * p.G + hl)) * AT_D + lg * 8;
+#pragma unroll
+        for (int ds = 0; ds < 4; ++ds) qd[rb][ds] = *reinterpret_cast<const uintx4*>(qp + 32 * ds);
+    }
 
     SplitRange sr;
     int n = p.n_nodes[b];
@@ -522,23 +612,48 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     //      stage's stay in flight), meet the others, then start stage k + 2.
     const unsigned kv_base = __builtin_amdgcn_readfirstlane(lds_address(&kv[0][0]));
     const int last_tok = sr.total - 1;
-    auto issue_stage = [&](int k) {
-        const unsigned buf = kv_base + (k & (AT_NBUF - 1)) * AT_STAGE_BYTES;
-        const int st = sr.st0 + k;
+    // A wavefront moves one page per stage: page 4 * stage + wave, 16 token rows of K and of V,
+    // four rows (1 KB) per instruction.  Lane (lg, l16) of instruction j fetches 16-byte chunk
+    // l16 of row 4 j + lg; which chunk of the row that is (the XOR swizzle) depends on the lane
+    // and on j only, so the lane's byte offsets inside a page are loop-invariant.
+    unsigned koff[4], voff[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int slot = 4 * wave_u + j;                         // 1 KB slot = 4 token rows
-            const int row = 4 * slot + lg;                           // token row within the stage
-            int t = st * AT_STAGE + row;
-            t = t < last_tok ? t : last_tok;                         // rows past the end re-read the last token
-            const int64_t off = static_cast<int64_t>(Tb[k * 4 + (slot >> 2)]) * p.page_stride +
-                                static_cast<int64_t>(t & 15) * p.token_stride +
-                                static_cast<int64_t>(g) * p.head_stride;
-            const int kchunk = l16 ^ (row & 15);
-            const int vchunk = (((l16 >> 1) ^ (row & 7)) << 1) | (l16 & 1);
-            load_global_to_lds_b128(static_cast<const __bf16*>(p.k) + off + kchunk * 8, buf + slot * 1024);
-            load_global_to_lds_b128(static_cast<const __bf16*>(p.v) + off + vchunk * 8,
-                                    buf + AT_STAGE * AT_ROW_BYTES + slot * 1024);
+    for (int j = 0; j < 4; ++j) {
+        const int row = 4 * j + lg;                                  // token row within the page
+        const int kchunk = l16 ^ row;
+        const int vchunk = (((l16 >> 1) ^ (row & 7)) << 1) | (l16 & 1);
+        const unsigned row_off = static_cast<unsigned>(row) * static_cast<unsigned>(p.token_stride) * 2u;
+        koff[j] = row_off + kchunk * 16;
+        voff[j] = row_off + vchunk * 16;
+    }
+    auto issue_stage = [&](int k) {
+        const unsigned buf = kv_base + (k & (AT_NBUF - 1)) * AT_STAGE_BYTES + wave_u * 4096;
+        const int t_page = (sr.st0 + k) * AT_STAGE + 16 * wave_u;   // first token of this wavefront's page
+        const int page = __builtin_amdgcn_readfirstlane(Tb[k * 4 + wave_u]);
+        const int64_t page_off = (static_cast<int64_t>(page) * p.page_stride + static_cast<int64_t>(g) * p.head_stride) * 2;
+        const unsigned char* kp = static_cast<const unsigned char*>(p.k) + page_off;
+        const unsigned char* vp = static_cast<const unsigned char*>(p.v) + page_off;
+        if (t_page + 15 <= last_tok) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                load_global_to_lds_b128(kp, koff[j], buf + j * 1024);
+                load_global_to_lds_b128(vp, voff[j], buf + AT_STAGE * AT_ROW_BYTES + j * 1024);
+            }
+        } else {
+            // the page holding the last token, or a page past it (its table entry then repeats
+            // the last page): rows past the end re-read the last token, whose values are finite
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = 4 * j + lg;
+                int t = t_page + row;
+                t = t < last_tok ? t : last_tok;
+                const int rowc = t & 15;
+                const int kchunk = l16 ^ row;
+                const int vchunk = (((l16 >> 1) ^ (row & 7)) << 1) | (l16 & 1);
+                const unsigned row_off = static_cast<unsigned>(rowc) * static_cast<unsigned>(p.token_stride) * 2u;
+                load_global_to_lds_b128(kp, row_off + kchunk * 16, buf + j * 1024);
+                load_global_to_lds_b128(vp, row_off + vchunk * 16, buf + AT_STAGE * AT_ROW_BYTES + j * 1024);
+            }
         }
     };
     auto advance = [&](int k) {
@@ -550,36 +665,20 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     if (n_st > 0) issue_stage(0);
     if (n_st > 1) issue_stage(1);
 
-    // ---- this wavefront's rows: Q^T into its registers, O^T accumulators to zero
-    const int r_base = rt * (AT_WAVES * 16 * MB) + wave_u * (16 * MB);
+    // ---- this wavefront's rows: Q' = bf16(Q * scale * log2 e) into AccVGPRs, O^T to zero
+    const float c_log2 = p.scale_log2e;
     WaveRows<MB> w;
     static_for<0, MB>([&](auto rb_) {
         GRAFT_CONST(rb, rb_);
-        const int r = r_base + rb * 16 + l16;
-        uintx4 qd[4];
-        if (r < p.R) {
-            const int i = r / p.G, hl = r - i * p.G;
-            const __bf16* qp = static_cast<const __bf16*>(p.q) +
-                ((static_cast<size_t>(b) * p.K_max + i) * p.Hq + (g * p.G + hl)) * AT_D + lg * 8;
-#pragma unroll
-            for (int ds = 0; ds < 4; ++ds) qd[ds] = *reinterpret_cast<const uintx4*>(qp + 32 * ds);
-        } else {
-#pragma unroll
-            for (int ds = 0; ds < 4; ++ds) qd[ds] = uintx4{0u, 0u, 0u, 0u};
-        }
-        if constexpr (rb < q_in_acc<MB>()) {
-            static_for<0, 16>([&](auto k_) {
-                GRAFT_CONST(k, k_);
-                acc_set_bits<q_reg<MB>(rb, 0) + k>(qd[k >> 2][k & 3]);
-            });
-        } else {
-#pragma unroll
-            for (int ds = 0; ds < 4; ++ds) w.qv[rb - q_in_acc<MB>()][ds] = __builtin_bit_cast(bf16x8, qd[ds]);
-        }
+        const float c_row = (r_base + rb * 16 + l16) < p.R ? c_log2 : 0.0f;
+        static_for<0, 16>([&](auto k_) {
+            GRAFT_CONST(k, k_);
+            acc_set_bits<q_reg<MB>(rb, 0) + k>(scale_bf16_pair(qd[rb][k >> 2][k & 3], c_row));
+        });
         w.m_ref[rb] = -INFINITY;
-        w.mneg[rb] = 0.0f;
         w.thr[rb] = -INFINITY;
-        w.l_run[rb] = 0.0f;
+        w.negm[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        w.lsum[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
         static_for<0, 32>([&](auto k_) {
             GRAFT_CONST(k, k_);
             acc_set<32 * rb + k>(0.0f);
@@ -590,69 +689,86 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     GRAFT_WAIT_VMCNT(0);
     GRAFT_MFMA_SETTLE();
 
-    const float c_log2 = p.scale_log2e;
+    uintx4 ones_bits;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) ones_bits[t] = opaque_bits(0x3f803f80u);    // 1.0 in both bf16 halves
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
     constexpr int K_OFF = 0, V_OFF = AT_STAGE * AT_ROW_BYTES, SUB = AT_SUB * AT_ROW_BYTES;
 
     // ---- fast loop, software pipelined over 32-token sub-tiles.  Step j: region 1 computes
-    //      the raw scores of sub-tile j (xr) while exponentiating sub-tile j-1 (xe -> pb);
-    //      region 2 accumulates P.V of sub-tile j-1 while turning xr into the exponents xe of
-    //      sub-tile j.  The first step exponentiates -inf (zero probabilities against the
-    //      zero-filled buffer 3), the last (drain) step computes scores nobody uses.  A row's
-    //      reference is the row maximum of the first tile that gives it a finite score and is
-    //      kept while later exponents stay below 2^AT_LAZY_LOG2; otherwise the wavefront leaves
-    //      for the slow loop below (exact running max, rescaling O with the vector ALUs).
-    floatx4 xr[MB][2], xe[MB][2];
+    //      the exponents of sub-tile j while exponentiating sub-tile j-1 (-> pb); region 2
+    //      accumulates P.V and the row sums of sub-tile j-1 while scanning the maxima of
+    //      sub-tile j.  Exponents ping-pong between xa (even j) and xb (odd j).  The first
+    //      step exponentiates -inf (zero probabilities against the zero-filled buffer 3), the
+    //      last (drain) step computes exponents nobody uses.  A row's reference is the row
+    //      maximum of the first tile that gives it a finite score and is kept while later
+    //      exponents stay below AT_LAZY_LOG2; otherwise the wavefront leaves for the slow loop
+    //      below (exact running max, rescaling O with the vector ALUs).
+    floatx4 xa[MB][2], xb[MB][2];
     uintx4 pb[MB];
     float lm[MB];
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
-        for (int c = 0; c < 2; ++c) xe[rb][c] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        for (int c = 0; c < 2; ++c) xb[rb][c] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 
     const int n_sub = 2 * n_st;
-    int j = 0;
+    int j = 0;                 // sub-tile whose exponents are pending when the fast loop is left
     bool slow = false;
-    for (; j <= n_sub; ++j) {
-        const bool live = j < n_sub;
-        if (live && (j & 1) == 0) advance(j >> 1);
-        const unsigned char* cur = kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB;
-        const unsigned char* prev = kv[((j - 1) >> 1) & (AT_NBUF - 1)] + ((j - 1) & 1) * SUB;
-        region_qk_exp<MB>(cur + K_OFF, w, xr, xe, pb, lane);
-        bool grow = region_pv_max<MB>(prev + V_OFF, w, pb, xr, xe, c_log2, lm, lane);
+    for (int k = 0; k <= n_st; ++k) {
+        reserve_acc_registers<MB>();    // nothing of the compiler's may live in the hand-managed AccVGPRs here
+        const bool live = k < n_st;
+        if (live) advance(k);
+        const unsigned char* cur = kv[k & (AT_NBUF - 1)];
+        const unsigned char* prev = kv[(k - 1) & (AT_NBUF - 1)];
+        const int t0 = (sr.st0 + k) * AT_STAGE;
+        // even sub-tile of stage k
+        region_qk_exp<MB>(cur + K_OFF, w, xa, xb, pb, lane);
+        bool grow = region_pv_max<MB>(prev + V_OFF + SUB, w, pb, xa, ones, lm, lane);
         if (!live) break;
-        const int t_sub0 = sr.st0 * AT_STAGE + j * AT_SUB;
-        if (t_sub0 + AT_SUB > sr.P)
-            grow = apply_tree_mask<MB>(xe, w, lm, lane, t_sub0, sr.P, sr.n, r_base, p.R, p.G, Ms);
-        if (grow && set_references<MB>(lm, w, xe)) { slow = true; break; }
+        if (t0 + AT_SUB > sr.P) grow = apply_tree_mask<MB>(xa, w, lm, lane, t0, sr.P, sr.n, r_base, p.R, p.G, Ms);
+        if (grow && set_references<MB>(lm, w, xa)) { slow = true; j = 2 * k; break; }
+        // odd sub-tile of stage k
+        region_qk_exp<MB>(cur + K_OFF + SUB, w, xb, xa, pb, lane);
+        grow = region_pv_max<MB>(cur + V_OFF, w, pb, xb, ones, lm, lane);
+        if (t0 + 2 * AT_SUB > sr.P)
+            grow = apply_tree_mask<MB>(xb, w, lm, lane, t0 + AT_SUB, sr.P, sr.n, r_base, p.R, p.G, Ms);
+        if (grow && set_references<MB>(lm, w, xb)) {
+            slow = true;
+            j = 2 * k + 1;
+#pragma unroll
+            for (int rb = 0; rb < MB; ++rb)
+#pragma unroll
+                for (int c = 0; c < 2; ++c) xa[rb][c] = xb[rb][c];
+            break;
+        }
     }
 
-    // ---- slow loop (rare): xe holds the exponents of sub-tile j against the old references and
+    // ---- slow loop (rare): xa holds the exponents of sub-tile j against the old references and
     //      lm their row maxima.  One sub-tile at a time, exact running max.
     if (slow) {
         while (true) {
+            reserve_acc_registers<MB>();
             const unsigned char* cur = kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB;
-            raise_references<MB>(lm, w, xe);
-            exp_only<MB>(xe, w, pb);
-            pv_only<MB>(cur + V_OFF, pb, lane);
+            raise_references<MB>(lm, w, xa);
+            exp_only<MB>(xa, pb);
+            pv_only<MB>(cur + V_OFF, w, pb, ones, lane);
             ++j;
             if (j >= n_sub) break;
             if ((j & 1) == 0) advance(j >> 1);
-            qk_only<MB>(kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB + K_OFF, w, xr, lane);
+            qk_only<MB>(kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB + K_OFF, w, xa, lane);
 #pragma unroll
             for (int rb = 0; rb < MB; ++rb) {
                 float mx = -INFINITY;
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        xe[rb][c][i] = __builtin_fmaf(xr[rb][c][i], c_log2, w.mneg[rb]);
-                        mx = fmaxf(mx, xe[rb][c][i]);
-                    }
+                    for (int i = 0; i < 4; ++i) mx = fmaxf(mx, xa[rb][c][i]);
                 lm[rb] = mx;
             }
             const int t_sub0 = sr.st0 * AT_STAGE + j * AT_SUB;
             if (t_sub0 + AT_SUB > sr.P)
-                apply_tree_mask<MB>(xe, w, lm, lane, t_sub0, sr.P, sr.n, r_base, p.R, p.G, Ms);
+                apply_tree_mask<MB>(xa, w, lm, lane, t_sub0, sr.P, sr.n, r_base, p.R, p.G, Ms);
 #pragma unroll
             for (int rb = 0; rb < MB; ++rb) {
                 float mx = lm[rb];
@@ -669,9 +785,6 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     static_for<0, MB>([&](auto rb_) {
         GRAFT_CONST(rb, rb_);
         const int r = r_base + rb * 16 + l16;
-        float l = w.l_run[rb];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
         float* op = p.ws_o + (part + r) * AT_D + 4 * lg;
         static_for<0, 8>([&](auto db_) {
             GRAFT_CONST(db, db_);
@@ -685,12 +798,15 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         if (lg == 0) {
             float* ml = p.ws_ml + (part + r) * 2;
             ml[0] = w.m_ref[rb];
-            ml[1] = l;
+            ml[1] = w.lsum[rb][0];
         }
     });
 }
 
 // Merge the splits of one output row: out = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
+// One wavefront per row.  Lane s holds split s's (m, l) and weight; the partial rows are then
+// read eight splits at a time with all eight loads in flight (no branch in between: a split
+// without keys has weight 0 and a zero partial row).
 __global__ __launch_bounds__(AT_THREADS) void tree_attn_combine_kernel(AttnParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t row = static_cast<int64_t>(blockIdx.x) * AT_WAVES + wave;   // over B*K_max*Hq
@@ -708,19 +824,36 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_combine_kernel(AttnParam
     }
     const int g = h / p.G, r = i * p.G + (h - g * p.G);
     const size_t base = (static_cast<size_t>(b) * p.Hkv + g) * p.n_splits * p.R_pad + r;
-    float mmax = -INFINITY;
-    for (int s = 0; s < p.n_splits; ++s)
-        mmax = fmaxf(mmax, p.ws_ml[(base + static_cast<size_t>(s) * p.R_pad) * 2]);
-    float acc0 = 0.f, acc1 = 0.f, den = 0.f;
-    for (int s = 0; s < p.n_splits; ++s) {
-        const size_t idx = base + static_cast<size_t>(s) * p.R_pad;
-        const float m = p.ws_ml[idx * 2], l = p.ws_ml[idx * 2 + 1];
-        if (m == -INFINITY) continue;                       // wavefront-uniform
-        const float w = __builtin_amdgcn_exp2f(m - mmax);
-        const float2 ov = *reinterpret_cast<const float2*>(p.ws_o + idx * AT_D + 2 * lane);
-        acc0 += w * ov.x;
-        acc1 += w * ov.y;
-        den += w * l;
+    const int ns = p.n_splits;                                   // <= AT_MAX_SPLITS = 64
+    float m_s = -INFINITY, l_s = 0.f;
+    if (lane < ns) {
+        const float2 ml = *reinterpret_cast<const float2*>(p.ws_ml + (base + static_cast<size_t>(lane) * p.R_pad) * 2);
+        m_s = ml.x;
+        l_s = ml.y;
+    }
+    float mmax = m_s;
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, sft));
+    const float w_s = m_s == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_s - mmax);
+    float den = w_s * l_s;
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) den += __shfl_xor(den, sft);
+    float acc0 = 0.f, acc1 = 0.f;
+    const float* orow = p.ws_o + base * AT_D + 2 * lane;
+    const size_t split_stride = static_cast<size_t>(p.R_pad) * AT_D;
+    for (int s0 = 0; s0 < ns; s0 += 8) {
+        float2 ov[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int sc = (s0 + u) < ns ? (s0 + u) : (ns - 1);
+            ov[u] = *reinterpret_cast<const float2*>(orow + sc * split_stride);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float wu = (s0 + u) < ns ? __shfl(w_s, s0 + u) : 0.f;
+            acc0 += wu * ov[u].x;
+            acc1 += wu * ov[u].y;
+        }
     }
     const float inv = den > 0.f ? 1.0f / den : 0.f;
     const unsigned lo = float_to_bf16_bits(acc0 * inv), hi = float_to_bf16_bits(acc1 * inv);
