@@ -167,8 +167,10 @@ int32_t graft_build_tree_mask(const int32_t* parent, const int32_t* n_nodes, con
  *                             256-byte aligned; contents are scratch.
  *
  * Requires D in {64,128}, Hq % Hkv == 0, Hq/Hkv <= 16, page_size == GRAFT_PAGE_SIZE,
- * 1 <= K_max <= GRAFT_MAX_NODES, max_pages >= 1, token_stride and head_stride
- * multiples of 8 elements, all sizes positive.
+ * 1 <= K_max <= GRAFT_MAX_NODES, 1 <= max_pages <= 262144 (4 Mi tokens),
+ * token_stride, head_stride and page_stride multiples of 8 elements,
+ * token_stride < 2^26, all sizes positive.  The workspace size depends on the
+ * device the calling thread has current (its compute-unit count picks the split).
  */
 size_t graft_tree_attn_workspace_bytes(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int32_t D,
                                        int32_t max_pages, int32_t dtype);

@@ -73,6 +73,7 @@ struct AttnParams {
     float* ws_ml;       // [B][Hkv][splits][R_pad][2]  (max in log2 units, sum)
     int64_t page_stride, token_stride, head_stride;
     int32_t max_pages, B, K_max, Hq, Hkv, G, R, R_pad, n_splits, n_row_tiles;
+    int32_t g_magic;    // ceil(2^16 / G): r / G == (r * g_magic) >> 16 for r < 4096, G <= 16
     float scale;        // softmax scale
     float scale_log2e;  // scale * log2(e)
 };
@@ -386,14 +387,14 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
 // tail): masked entries become -inf; the lane-local maxima are recomputed.
 template <int MB>
 __device__ __forceinline__ bool apply_tree_mask(floatx4 (&x)[MB][2], const WaveRows<MB>& w, float (&lm)[MB],
-                                                int lane, int t_sub0, int P, int n, int r_base, int R, int G,
+                                                int lane, int t_sub0, int P, int n, int r_base, int R, int g_magic,
                                                 const unsigned* __restrict__ Ms) {
     const int l16 = lane & 15, lg = lane >> 4;
     bool grow = false;
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) {
         const int r = r_base + rb * 16 + l16;
-        const int node = r / G;
+        const int node = (r * g_magic) >> 16;              // r / G
         const bool live = r < R && node < n;
         const int nd = live ? node : 0;
         unsigned wd[4];
@@ -556,8 +557,16 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lg = lane >> 4;
-    const int split = blockIdx.x % p.n_splits, rt = blockIdx.x / p.n_splits;
-    const int g = blockIdx.y, b = blockIdx.z;
+    // Workgroups go to the 8 XCDs (each with its own L2) round-robin by their linear index.
+    // The row tiles of one (sequence, KV head, split) read the same keys and values: they get
+    // the same XCD and neighbouring slots on it, so that they run side by side and all but the
+    // first reader find the stage in that XCD's L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int rt = slot % p.n_row_tiles;
+    const int unit = (slot / p.n_row_tiles) * 8 + xcd;           // over B * Hkv * n_splits
+    if (unit >= p.B * p.Hkv * p.n_splits) return;                 // grid padding (whole workgroup)
+    const int split = unit % p.n_splits;
+    const int g = (unit / p.n_splits) % p.Hkv, b = unit / (p.n_splits * p.Hkv);
 
     // Q rows of this wavefront: the loads are issued first so that their latency overlaps the
     // set-up below (rows past R read row 0 and are zeroed when converted)
@@ -567,7 +576,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     for (int rb = 0; rb < MB; ++rb) {
         const int r = r_base + rb * 16 + l16;
         const int rc = r < p.R ? r : 0;
-        const int i = rc / p.G, hl = rc - i * p.G;
+        const int i = (rc * p.g_magic) >> 16, hl = rc - i * p.G;     // i = rc / G
         const __bf16* qp = static_cast<const __bf16*>(p.q) +
             ((static_cast<size_t>(b) * p.K_max + i) * p.Hq + (g * p.G + hl)) * AT_D + lg * 8;
 #pragma unroll
@@ -626,10 +635,13 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         koff[j] = row_off + kchunk * 16;
         voff[j] = row_off + vchunk * 16;
     }
+    int tb_next = Tb[wave_u];       // stages are issued in order: the next stage's table entry is read one stage early
     auto issue_stage = [&](int k) {
         const unsigned buf = kv_base + (k & (AT_NBUF - 1)) * AT_STAGE_BYTES + wave_u * 4096;
         const int t_page = (sr.st0 + k) * AT_STAGE + 16 * wave_u;   // first token of this wavefront's page
-        const int page = __builtin_amdgcn_readfirstlane(Tb[k * 4 + wave_u]);
+        const int page = __builtin_amdgcn_readfirstlane(tb_next);
+        const int nxt = (k + 1) * 4 + wave_u;
+        tb_next = Tb[nxt < AT_MAX_SPLIT_PAGES ? nxt : AT_MAX_SPLIT_PAGES - 1];
         const int64_t page_off = (static_cast<int64_t>(page) * p.page_stride + static_cast<int64_t>(g) * p.head_stride) * 2;
         const unsigned char* kp = static_cast<const unsigned char*>(p.k) + page_off;
         const unsigned char* vp = static_cast<const unsigned char*>(p.v) + page_off;
@@ -647,19 +659,24 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
                 const int row = 4 * j + lg;
                 int t = t_page + row;
                 t = t < last_tok ? t : last_tok;
-                const int rowc = t & 15;
                 const int kchunk = l16 ^ row;
                 const int vchunk = (((l16 >> 1) ^ (row & 7)) << 1) | (l16 & 1);
-                const unsigned row_off = static_cast<unsigned>(rowc) * static_cast<unsigned>(p.token_stride) * 2u;
+                const unsigned row_off = static_cast<unsigned>(t & 15) * static_cast<unsigned>(p.token_stride) * 2u;
                 load_global_to_lds_b128(kp, row_off + kchunk * 16, buf + j * 1024);
                 load_global_to_lds_b128(vp, row_off + vchunk * 16, buf + AT_STAGE * AT_ROW_BYTES + j * 1024);
             }
         }
     };
-    auto advance = [&](int k) {
+    // arrive(k): wait for this wavefront's transfers of stage k (those of stage k + 1 stay in
+    // flight) and meet the other wavefronts.  After it stage k can be read and the buffer of
+    // stage k + 2 (last read in step k - 1) can be refilled.  advance(k) also starts stage k + 2.
+    auto arrive = [&](int k) {
         if (k + 1 < n_st) GRAFT_WAIT_VMCNT(AT_LOADS_PER_STAGE);
         else GRAFT_WAIT_VMCNT(0);
         lds_barrier();
+    };
+    auto advance = [&](int k) {
+        arrive(k);
         if (k + 2 < n_st) issue_stage(k + 2);
     };
     if (n_st > 0) issue_stage(0);
@@ -718,6 +735,11 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     for (int k = 0; k <= n_st; ++k) {
         reserve_acc_registers<MB>();    // nothing of the compiler's may live in the hand-managed AccVGPRs here
         const bool live = k < n_st;
+        // All transfers of stage k + 2 are issued right after the barrier.  The compute unit's
+        // address path takes about 16 cycles per 1 KB transfer, so the four wavefronts hold
+        // each other up for about 500 cycles here; measured alternatives were slower (a
+        // transfer issued while MFMAs are in flight stalls the wavefront for far longer,
+        // whether the transfers are spread over the step or staggered by wavefront).
         if (live) advance(k);
         const unsigned char* cur = kv[k & (AT_NBUF - 1)];
         const unsigned char* prev = kv[(k - 1) & (AT_NBUF - 1)];
@@ -726,13 +748,13 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         region_qk_exp<MB>(cur + K_OFF, w, xa, xb, pb, lane);
         bool grow = region_pv_max<MB>(prev + V_OFF + SUB, w, pb, xa, ones, lm, lane);
         if (!live) break;
-        if (t0 + AT_SUB > sr.P) grow = apply_tree_mask<MB>(xa, w, lm, lane, t0, sr.P, sr.n, r_base, p.R, p.G, Ms);
+        if (t0 + AT_SUB > sr.P) grow = apply_tree_mask<MB>(xa, w, lm, lane, t0, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
         if (grow && set_references<MB>(lm, w, xa)) { slow = true; j = 2 * k; break; }
         // odd sub-tile of stage k
         region_qk_exp<MB>(cur + K_OFF + SUB, w, xb, xa, pb, lane);
         grow = region_pv_max<MB>(cur + V_OFF, w, pb, xb, ones, lm, lane);
         if (t0 + 2 * AT_SUB > sr.P)
-            grow = apply_tree_mask<MB>(xb, w, lm, lane, t0 + AT_SUB, sr.P, sr.n, r_base, p.R, p.G, Ms);
+            grow = apply_tree_mask<MB>(xb, w, lm, lane, t0 + AT_SUB, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
         if (grow && set_references<MB>(lm, w, xb)) {
             slow = true;
             j = 2 * k + 1;
@@ -768,7 +790,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             }
             const int t_sub0 = sr.st0 * AT_STAGE + j * AT_SUB;
             if (t_sub0 + AT_SUB > sr.P)
-                apply_tree_mask<MB>(xa, w, lm, lane, t_sub0, sr.P, sr.n, r_base, p.R, p.G, Ms);
+                apply_tree_mask<MB>(xa, w, lm, lane, t_sub0, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
 #pragma unroll
             for (int rb = 0; rb < MB; ++rb) {
                 float mx = lm[rb];
@@ -803,10 +825,30 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     });
 }
 
+// Weighted sum of one row's partial results, U splits per step with all U loads in flight.
+template <int U>
+__device__ __forceinline__ void combine_rows(const float* orow, size_t split_stride, int ns, float w_s,
+                                             float& acc0, float& acc1) {
+    for (int s0 = 0; s0 < ns; s0 += U) {
+        float2 ov[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int sc = (s0 + u) < ns ? (s0 + u) : (ns - 1);
+            ov[u] = *reinterpret_cast<const float2*>(orow + sc * split_stride);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float wu = (s0 + u) < ns ? __shfl(w_s, s0 + u) : 0.f;
+            acc0 += wu * ov[u].x;
+            acc1 += wu * ov[u].y;
+        }
+    }
+}
+
 // Merge the splits of one output row: out = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
 // One wavefront per row.  Lane s holds split s's (m, l) and weight; the partial rows are then
-// read eight splits at a time with all eight loads in flight (no branch in between: a split
-// without keys has weight 0 and a zero partial row).
+// read up to eight splits at a time with all their loads in flight (no branch in between: a
+// split without keys has weight 0 and a zero partial row).
 __global__ __launch_bounds__(AT_THREADS) void tree_attn_combine_kernel(AttnParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t row = static_cast<int64_t>(blockIdx.x) * AT_WAVES + wave;   // over B*K_max*Hq
@@ -841,20 +883,9 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_combine_kernel(AttnParam
     float acc0 = 0.f, acc1 = 0.f;
     const float* orow = p.ws_o + base * AT_D + 2 * lane;
     const size_t split_stride = static_cast<size_t>(p.R_pad) * AT_D;
-    for (int s0 = 0; s0 < ns; s0 += 8) {
-        float2 ov[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int sc = (s0 + u) < ns ? (s0 + u) : (ns - 1);
-            ov[u] = *reinterpret_cast<const float2*>(orow + sc * split_stride);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float wu = (s0 + u) < ns ? __shfl(w_s, s0 + u) : 0.f;
-            acc0 += wu * ov[u].x;
-            acc1 += wu * ov[u].y;
-        }
-    }
+    if (ns >= 8) combine_rows<8>(orow, split_stride, ns, w_s, acc0, acc1);
+    else if (ns >= 4) combine_rows<4>(orow, split_stride, ns, w_s, acc0, acc1);
+    else combine_rows<2>(orow, split_stride, ns, w_s, acc0, acc1);
     const float inv = den > 0.f ? 1.0f / den : 0.f;
     const unsigned lo = float_to_bf16_bits(acc0 * inv), hi = float_to_bf16_bits(acc1 * inv);
     *reinterpret_cast<unsigned*>(outp) = lo | (hi << 16);
@@ -984,6 +1015,28 @@ struct AttnPlan {
     size_t ws_o_bytes, ws_bytes;
 };
 
+// Compute units of the current device (256 when it cannot be asked, e.g. without a GPU).
+static int device_compute_units() {
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cached = n;
+        else
+            cached = 256;
+        (void)hipGetLastError();
+    }
+    return cached;
+}
+
+// Launch shape of the MFMA path.  One workgroup per compute unit is resident at a time, so
+// the job runs in ceil(workgroups / CUs) rounds, each as long as one workgroup's pass: a
+// fixed part (set-up, Q conversion, writing the partial results) plus its stages.  The
+// numbers are cycles measured on MI355X (per stage about 680 MB + 1100, fixed about
+// 3300 MB + 8000); the plan takes the row tiling (MB <= 5 row blocks per wavefront) and the
+// number of splits (<= 64, each with at most AT_MAX_SPLIT_PAGES pages) that make the
+// estimate smallest.  It depends on the capacity max_pages, not on the actual lengths.
 static AttnPlan make_plan(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int32_t D, int32_t max_pages,
                           int32_t dtype) {
     AttnPlan pl{};
@@ -991,19 +1044,32 @@ static AttnPlan make_plan(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
     if (!pl.mfma) return pl;
     const int R = K_max * (Hq / Hkv);
     const int rows_per_mb = AT_WAVES * 16;                       // rows a workgroup covers per MB
-    pl.n_row_tiles = (R + rows_per_mb * AT_MAX_MB - 1) / (rows_per_mb * AT_MAX_MB);
-    pl.mb = (R + pl.n_row_tiles * rows_per_mb - 1) / (pl.n_row_tiles * rows_per_mb);
+    const int64_t stages = (static_cast<int64_t>(max_pages) * GRAFT_PAGE_SIZE + AT_STAGE - 1) / AT_STAGE;
+    const int64_t min_splits = (stages * (AT_STAGE / GRAFT_PAGE_SIZE) + AT_MAX_SPLIT_PAGES - 1) / AT_MAX_SPLIT_PAGES;
+    const int64_t cus = device_compute_units();
+    const int rt_min = (R + rows_per_mb * AT_MAX_MB - 1) / (rows_per_mb * AT_MAX_MB);
+    const int rt_max = (R + rows_per_mb - 1) / rows_per_mb;
+    double best = -1.0;
+    for (int rt = rt_min; rt <= rt_max && rt <= rt_min + 3; ++rt) {
+        const int mb = (R + rt * rows_per_mb - 1) / (rt * rows_per_mb);
+        const double c_stage = 680.0 * mb + 1100.0, c_fixed = 3300.0 * mb + 8000.0;
+        const int64_t units = static_cast<int64_t>(B) * Hkv * rt;
+        int64_t s_hi = stages < AT_MAX_SPLITS ? stages : AT_MAX_SPLITS;
+        if (s_hi < 1) s_hi = 1;
+        for (int64_t sp = min_splits < 1 ? 1 : min_splits; sp <= s_hi; ++sp) {
+            const int64_t rounds = (units * sp + cus - 1) / cus;
+            const int64_t per = (stages + sp - 1) / sp;
+            const double cost = rounds * (c_fixed + per * c_stage) + 300.0 * sp;
+            if (best < 0.0 || cost < best) {
+                best = cost;
+                pl.n_row_tiles = rt;
+                pl.mb = mb;
+                pl.n_splits = static_cast<int>(sp);
+            }
+        }
+    }
     pl.r_pad = pl.n_row_tiles * pl.mb * rows_per_mb;
-    const int stages = (max_pages * GRAFT_PAGE_SIZE + AT_STAGE - 1) / AT_STAGE;
-    const int units = B * Hkv * pl.n_row_tiles;
-    int splits = (256 + units - 1) / units;                      // one workgroup per CU
-    if (splits > stages) splits = stages;
-    if (splits > AT_MAX_SPLITS) splits = AT_MAX_SPLITS;
-    if (splits < 1) splits = 1;
-    const int min_splits = (stages * (AT_STAGE / GRAFT_PAGE_SIZE) + AT_MAX_SPLIT_PAGES - 1) / AT_MAX_SPLIT_PAGES;
-    if (splits < min_splits) splits = min_splits;       // a split's block-table slice must fit in LDS
-    pl.n_splits = splits;
-    const size_t rows = static_cast<size_t>(B) * Hkv * splits * pl.r_pad;
+    const size_t rows = static_cast<size_t>(B) * Hkv * pl.n_splits * pl.r_pad;
     pl.ws_o_bytes = rows * AT_D * sizeof(float);
     pl.ws_bytes = pl.ws_o_bytes + rows * 2 * sizeof(float);
     return pl;
@@ -1012,7 +1078,7 @@ static AttnPlan make_plan(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
 static bool attn_shape_ok(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int32_t D, int32_t max_pages) {
     return B >= 1 && B <= 65535 && K_max >= 1 && K_max <= GRAFT_MAX_NODES && Hq >= 1 && Hkv >= 1 &&
            Hkv <= 65535 && Hq % Hkv == 0 && Hq / Hkv <= 16 && (D == 64 || D == 128) && max_pages >= 1 &&
-           max_pages <= (1 << 26);
+           max_pages <= AT_MAX_SPLITS * AT_MAX_SPLIT_PAGES;    // 64 splits x 4096 pages = 4 Mi tokens
 }
 
 // Profiling hook state (per host thread): event pairs recorded around the main kernel.
@@ -1062,7 +1128,7 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
         return GRAFT_ERR_NULL;
     if (dtype != GRAFT_F32 && dtype != GRAFT_BF16) return GRAFT_ERR_DTYPE;
     if (!attn_shape_ok(B, K_max, Hq, Hkv, D, max_pages) || page_size != GRAFT_PAGE_SIZE ||
-        page_stride < 1 || token_stride < D || head_stride < D || token_stride % 8 != 0 ||
+        page_stride < 1 || token_stride < D || token_stride >= (1 << 26) || head_stride < D || token_stride % 8 != 0 ||
         head_stride % 8 != 0 || page_stride % 8 != 0 || !(scale > 0.f) || !(scale < 1e30f))
         return GRAFT_ERR_SHAPE;
     const AttnPlan pl = make_plan(B, K_max, Hq, Hkv, D, max_pages, dtype);
@@ -1075,6 +1141,7 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     p.page_stride = page_stride; p.token_stride = token_stride; p.head_stride = head_stride;
     p.max_pages = max_pages; p.B = B; p.K_max = K_max; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
     p.R = K_max * p.G;
+    p.g_magic = (65536 + p.G - 1) / p.G;
     p.scale = scale;
     p.scale_log2e = scale * 1.4426950408889634f;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1095,7 +1162,8 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     p.R_pad = pl.r_pad; p.n_splits = pl.n_splits; p.n_row_tiles = pl.n_row_tiles;
     p.ws_o = static_cast<float*>(workspace);
     p.ws_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + pl.ws_o_bytes);
-    dim3 grid(pl.n_splits * pl.n_row_tiles, Hkv, B);
+    const int64_t n_units = static_cast<int64_t>(B) * Hkv * pl.n_splits;
+    dim3 grid(static_cast<unsigned>(((n_units + 7) / 8) * 8 * pl.n_row_tiles));
     prof_record(true, s);
     switch (pl.mb) {
         case 1: launch_mfma<1>(p, grid, s); break;
