@@ -7,7 +7,7 @@ on one stream, inputs resident in HBM.  Prints ONE JSON line:
   metric / value : tree-verify attention algorithmic bytes per step divided by the whole
                    step's time (GB/s), plus us per step in extra keys;
   roofline       : the dominant kernel (the MFMA tree-attention kernel) timed with HIP
-                   events recorded by the library right around that kernel;
+                   events that the library attaches to that kernel's dispatch;
   cpu_baseline   : the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run five plain 1 GiB -> 1 GiB elementwise copies and exit: the reference that the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -88,6 +91,16 @@ def main():
         sys.exit(1)
     graft.load_library()                       # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = (1 << 30) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)       # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_launch": n * 4,
+                          "bytes_written_per_launch": n * 4, "launches": 5}))
+        return
     hip = Hip()
 
     w = inputs.get_workload(args.workload)
@@ -166,7 +179,7 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly `steps` steps; the library records an event pair around every
+    # ---- timed region: exactly `steps` steps; the library attaches an event pair to every
     #      main attention kernel in it
     n_ev = steps * w.layers
     ev_a = (ctypes.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)])

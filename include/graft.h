@@ -187,10 +187,10 @@ int32_t graft_tree_attn(const void* q, const void* k_cache, const void* v_cache,
  * graft_attn_profile_events - measurement hook for benchmarks (not part of the
  * method).  start_events / stop_events are host arrays of n hipEvent_t created by
  * the caller.  While set, the i-th graft_tree_attn call made afterwards on this
- * host thread (i < n) records start_events[i] on the stream right before its main
- * attention kernel and stop_events[i] right after it (before the split-merge
- * kernel), so the caller can read that kernel's own duration.  n = 0 clears the
- * hook.  The arrays must stay alive until it is cleared.
+ * host thread (i < n) attaches start_events[i] / stop_events[i] to the dispatch of
+ * its main attention kernel (not the split-merge kernel): after the stream has
+ * been synchronised their elapsed time is that kernel's own duration.  n = 0
+ * clears the hook.  The arrays must stay alive until it is cleared.
  */
 int32_t graft_attn_profile_events(void** start_events, void** stop_events, int32_t n);
 

@@ -40,6 +40,8 @@
 //     an independent GPU cross-check of path (1).
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "common.h"
 
 namespace graft {
@@ -1081,21 +1083,21 @@ static bool attn_shape_ok(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
            max_pages <= AT_MAX_SPLITS * AT_MAX_SPLIT_PAGES;    // 64 splits x 4096 pages = 4 Mi tokens
 }
 
-// Profiling hook state (per host thread): event pairs recorded around the main kernel.
+// Profiling hook state (per host thread): event pairs attached to the main kernel's dispatch
+// (hipExtLaunchKernelGGL: the events then carry the kernel's own begin and end time stamps,
+// without the dispatch latency that events recorded around a launch would include).
 static thread_local hipEvent_t* g_prof_start = nullptr;
 static thread_local hipEvent_t* g_prof_stop = nullptr;
 static thread_local int32_t g_prof_n = 0, g_prof_i = 0;
 
-static void prof_record(bool start, hipStream_t s) {
+template <class Kernel>
+static void launch_main(Kernel kernel, dim3 grid, dim3 block, hipStream_t s, const AttnParams& p) {
     if (g_prof_i < g_prof_n) {
-        (void)hipEventRecord(start ? g_prof_start[g_prof_i] : g_prof_stop[g_prof_i], s);
-        if (!start) ++g_prof_i;
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, s, g_prof_start[g_prof_i], g_prof_stop[g_prof_i], 0, p);
+        ++g_prof_i;
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, p);
     }
-}
-
-template <int MB>
-static void launch_mfma(const AttnParams& p, dim3 grid, hipStream_t s) {
-    hipLaunchKernelGGL(tree_attn_mfma_kernel<MB>, grid, dim3(AT_THREADS), 0, s, p);
 }
 
 }  // namespace graft
@@ -1148,14 +1150,12 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
 
     if (!pl.mfma) {
         dim3 grid(Hq, K_max, B);
-        prof_record(true, s);
         if (dtype == GRAFT_F32) {
-            if (D == 64) hipLaunchKernelGGL((tree_attn_simple_kernel<float, 64>), grid, dim3(SM_THREADS), 0, s, p);
-            else hipLaunchKernelGGL((tree_attn_simple_kernel<float, 128>), grid, dim3(SM_THREADS), 0, s, p);
+            if (D == 64) launch_main(tree_attn_simple_kernel<float, 64>, grid, dim3(SM_THREADS), s, p);
+            else launch_main(tree_attn_simple_kernel<float, 128>, grid, dim3(SM_THREADS), s, p);
         } else {
-            hipLaunchKernelGGL((tree_attn_simple_kernel<unsigned short, 64>), grid, dim3(SM_THREADS), 0, s, p);
+            launch_main(tree_attn_simple_kernel<unsigned short, 64>, grid, dim3(SM_THREADS), s, p);
         }
-        prof_record(false, s);
         return check_launch();
     }
 
@@ -1164,15 +1164,13 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     p.ws_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + pl.ws_o_bytes);
     const int64_t n_units = static_cast<int64_t>(B) * Hkv * pl.n_splits;
     dim3 grid(static_cast<unsigned>(((n_units + 7) / 8) * 8 * pl.n_row_tiles));
-    prof_record(true, s);
     switch (pl.mb) {
-        case 1: launch_mfma<1>(p, grid, s); break;
-        case 2: launch_mfma<2>(p, grid, s); break;
-        case 3: launch_mfma<3>(p, grid, s); break;
-        case 4: launch_mfma<4>(p, grid, s); break;
-        default: launch_mfma<5>(p, grid, s); break;
+        case 1: launch_main(tree_attn_mfma_kernel<1>, grid, dim3(AT_THREADS), s, p); break;
+        case 2: launch_main(tree_attn_mfma_kernel<2>, grid, dim3(AT_THREADS), s, p); break;
+        case 3: launch_main(tree_attn_mfma_kernel<3>, grid, dim3(AT_THREADS), s, p); break;
+        case 4: launch_main(tree_attn_mfma_kernel<4>, grid, dim3(AT_THREADS), s, p); break;
+        default: launch_main(tree_attn_mfma_kernel<5>, grid, dim3(AT_THREADS), s, p); break;
     }
-    prof_record(false, s);
     int32_t rc = check_launch();
     if (rc != GRAFT_OK) return rc;
     const int64_t n_rows = static_cast<int64_t>(B) * K_max * Hq;
