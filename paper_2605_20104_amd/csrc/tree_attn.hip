@@ -7,33 +7,37 @@
 //     that is streamed, so K and V are read from HBM once per head; the
 //     arithmetic intensity is R flop per byte, which puts the tree-verify shapes
 //     (R = 160..768) around the MFMA/HBM ridge of the chip.
-//       grid  = (splits * row_tiles, Hkv, B), 512 threads = 8 wavefronts,
-//               one workgroup per CU, two wavefronts per SIMD (<= 256 VGPRs each)
-//               so that one wavefront's softmax VALU work overlaps the other's MFMAs.
-//       rows  : a wavefront owns 16*MB query rows (MB <= 3 MFMA row blocks);
-//               wavefronts 0..3 take MBA blocks and 4..7 take MBB <= MBA, so that
-//               e.g. 320 rows = 16 * 4 * (3 + 2) load the four SIMDs evenly.  Q stays
-//               in registers for the whole kernel, O accumulates in registers as
-//               O^T tiles.
+//       grid  : one workgroup of 256 threads (4 wavefronts, one per SIMD, 512
+//               registers each) per (row tile, split, KV head, sequence); the
+//               host plan sizes it to about one workgroup per compute unit.
+//       rows  : a wavefront owns 16*MB query rows (MB <= 5 MFMA row blocks).  Its
+//               O^T accumulators and the Q operand live in hand-placed AccVGPRs
+//               and are only touched by inline-asm MFMAs inside the loop.
 //       K/V   : 64-token stages (4 pages) go global -> LDS directly (no register
-//               staging), double buffered, one barrier per stage; K rows are
-//               XOR-swizzled at 16 B and V rows at 32 B so that the MFMA operand
-//               reads spread over all banks.
-//       QK^T  : S^T = K * Q^T with v_mfma_f32_16x16x32_bf16, so each lane holds
-//               scores of ONE query row (column l%16): the row max needs only two
-//               cross-lane steps and the probabilities are already laid out as
-//               the B operand of the second product (no LDS round trip).
-//       PV    : O^T = V^T * P^T; the V^T operand (contraction over tokens, which
+//               staging) into a ring of four buffers, two stages in flight, one
+//               LDS-only barrier per stage; K rows are XOR-swizzled at 16 B and
+//               V rows at 32 B so that the MFMA operand reads spread over all banks.
+//       QK^T  : X^T = K * Q'^T - m with v_mfma_f32_16x16x32_bf16, where
+//               Q' = bf16(Q * scale * log2 e) and the negated row reference m is
+//               the accumulator input: the result is the argument of exp2.  Each
+//               lane holds exponents of ONE query row (column l%16), and the
+//               packed probabilities are already laid out as the B operand of
+//               the second product (no LDS round trip).
+//       PV    : O^T += V^T * P^T; the V^T operand (contraction over tokens, which
 //               are strided in memory) comes from the gfx950 LDS transpose read
 //               ds_read_b64_tr_b16: a 16-lane group turns a 4-token x 16-dim
-//               block into "lane = dim, 4 tokens packed".
+//               block into "lane = dim, 4 tokens packed".  Row sums: one more
+//               MFMA per row block with an all-ones A operand.
+//       pipeline: over 32-token sub-tiles, MFMAs of one sub-tile interleaved slot
+//               by slot with the exp2 / pack / max work of its neighbours.
 //       mask  : only sub-tiles that reach past the prefix take the masked path
 //               (ancestor bits from graft_build_tree_mask); the prefix is dense.
-//       softmax: running max with a lazy threshold (the accumulators are only
-//               rescaled when the row max grows by more than 2^8), exp2 with the
-//               scale folded into one FMA.
-//     Partials (unnormalised O, max, sum) go to the workspace; a small combine
-//     kernel merges the splits and writes bf16.
+//       softmax: a row's reference is the maximum of the first sub-tile that gives
+//               it a finite score and is kept while later exponents stay below
+//               2^24; beyond that the wavefront switches to an exact online
+//               softmax loop that rescales the accumulators.
+//     Partials (unnormalised O, reference, sum) go to the workspace; a small
+//     combine kernel merges the splits and writes bf16.
 //
 // (2) everything else (fp32 storage, or D = 64): a plain one-workgroup-per-
 //     (node, head) kernel in fp32.  It serves the tiny fp32 configuration and as
