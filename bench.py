@@ -73,6 +73,12 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the step from a captured HIP graph and report its time per step")
+    ap.add_argument("--no-rotate", action="store_true",
+                    help="reuse one KV buffer for every layer (Infinity-Cache-resident figure for small workloads)")
+    ap.add_argument("--logits", action="store_true",
+                    help="graft_accept takes fp32 logits [B,K,V] (argmax scan on the GPU) instead of target ids")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run five plain 1 GiB -> 1 GiB elementwise copies and exit: the reference that the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
@@ -109,10 +115,10 @@ def main():
     att_bytes, att_flops = attention_bytes_and_flops(w)
 
     # ---- inputs -> HBM
-    s = inputs.make_step_inputs(w)
+    s = inputs.make_step_inputs(w, with_logits=args.logits)
     kv_bytes_one = att_bytes  # per layer
     n_kv = max(w.distinct_kv_layers, 1)
-    while n_kv * kv_bytes_one < 2 * MALL_BYTES and n_kv < 64 and w.name != "c1":
+    while n_kv * kv_bytes_one < 2 * MALL_BYTES and n_kv < 64 and w.name != "c1" and not args.no_rotate:
         n_kv += 1                              # rotate buffers so that every launch streams from HBM
     att = inputs.make_attention_inputs(w, kv_buffers=n_kv, q_layers=min(w.layers, 4))
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
@@ -161,6 +167,10 @@ def main():
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     layer_counter = [0]
+    logits = torch.from_numpy(s["logits"]).cuda() if args.logits else None
+    acc_ws = (torch.empty(graft.graft_accept_workspace_bytes(B, K, w.vocab), dtype=torch.uint8, device=dev)
+              if args.logits else None)
+    ids_out = torch.empty((B, K), dtype=torch.int32, device=dev)
 
     def step():
         graft.graft_retrieve(d["ctx"], d["ctx_len"], w.n_min, w.n_max, w.C, w.m, d["tail"], d["tail_len"],
@@ -172,30 +182,43 @@ def main():
             graft.graft_tree_attn(q[l % len(q)], kc[i % n_kv], vc[i % n_kv], att["strides"], table,
                                   d["prefix_len"], d["n_nodes"], mask_out["mask"], w.Hkv, att["scale"],
                                   out=o, workspace=ws)
-        graft.graft_accept(d["parent"], d["tokens"], d["n_nodes"], depth_cap, target_ids=d["target_ids"],
-                           out=acc_out)
+        accept()
 
+    def accept():
+        if args.logits:
+            lib_.graft_accept(d["parent"].data_ptr(), d["tokens"].data_ptr(), d["n_nodes"].data_ptr(),
+                              logits.data_ptr(), w.vocab, ids_out.data_ptr(), B, K, depth_cap,
+                              acc_out["accept_len"].data_ptr(), acc_out["best_node"].data_ptr(),
+                              acc_out["path"].data_ptr(), acc_out["out_tokens"].data_ptr(),
+                              acc_out["status"].data_ptr(), acc_ws.data_ptr(), acc_ws.numel(),
+                              torch.cuda.current_stream().cuda_stream)
+        else:
+            graft.graft_accept(d["parent"], d["tokens"], d["n_nodes"], depth_cap, target_ids=d["target_ids"],
+                               out=acc_out)
+
+    lib_ = graft.load_library()
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly `steps` steps; the library attaches an event pair to every
-    #      main attention kernel in it
-    n_ev = steps * w.layers
+    # ---- timed region: exactly `steps` steps; the library attaches an event pair to the main
+    #      attention kernel of its first n_ev attention calls
+    n_ev = min(steps * w.layers, 256)      # attaching events costs host time per launch: bound it
     ev_a = (ctypes.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)])
     ev_b = (ctypes.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)])
     lib = graft.load_library()
     assert lib.graft_attn_profile_events(ev_a, ev_b, n_ev) == 0
-    t_a, t_b = hip.event(), hip.event()
+    marks = [hip.event() for _ in range(steps + 1)]          # step boundaries (for the percentiles)
     torch.cuda.synchronize()
-    hip.record(t_a, stream)
+    hip.record(marks[0], stream)
     t0 = time.perf_counter()
-    for _ in range(steps):
+    for i in range(steps):
         step()
-    hip.record(t_b, stream)
+        hip.record(marks[i + 1], stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    total_ms = hip.elapsed_ms(t_a, t_b)
+    total_ms = hip.elapsed_ms(marks[0], marks[steps])
+    step_us = np.array([hip.elapsed_ms(marks[i], marks[i + 1]) for i in range(steps)]) * 1e3
     lib.graft_attn_profile_events(None, None, 0)
     kern_ms = np.array([hip.elapsed_ms(ev_a[i], ev_b[i]) for i in range(n_ev)])
     ms_per_step = total_ms / steps
@@ -220,9 +243,30 @@ def main():
         "tree_attn_layer": time_call(lambda: graft.graft_tree_attn(
             q[0], kc[layer_counter[0] % n_kv], vc[layer_counter[0] % n_kv], att["strides"], table,
             d["prefix_len"], d["n_nodes"], mask_out["mask"], w.Hkv, att["scale"], out=o, workspace=ws)),
-        "accept": time_call(lambda: graft.graft_accept(d["parent"], d["tokens"], d["n_nodes"], depth_cap,
-                                                       target_ids=d["target_ids"], out=acc_out)),
+        "accept": time_call(accept),
     }
+
+    # ---- optional: the same step replayed from a captured HIP graph (launch overhead removed)
+    graph_us = None
+    if args.graph:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            step()                                   # warm-up on the capture stream
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            step()
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        a, b_ = hip.event(), hip.event()
+        cur = torch.cuda.current_stream().cuda_stream
+        hip.record(a, cur)
+        for _ in range(steps):
+            g.replay()
+        hip.record(b_, cur)
+        torch.cuda.synchronize()
+        graph_us = hip.elapsed_ms(a, b_) * 1e3 / steps
 
     # ---- sanity of the timed outputs against the generator's planted answers
     torch.cuda.synchronize()
@@ -230,6 +274,8 @@ def main():
     for b in range(B):
         assert pos[b].tolist() == s["planted_pos"][b][:w.C], "retrieval lost the planted chains"
     assert torch.isfinite(o.float()).all()
+    if args.logits:
+        assert torch.equal(ids_out, d["target_ids"]), "argmax over the logits lost the planted target ids"
 
     step_att_bytes = att_bytes * w.layers
     value = step_att_bytes / (ms_per_step * 1e-3) / 1e9
@@ -246,6 +292,8 @@ def main():
         "value": round(value, 2), "unit": "GB/s",
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "us_per_step": round(ms_per_step * 1e3, 2),
+        "us_per_step_p10_p50_p90": [round(float(np.percentile(step_us, q)), 2) for q in (10, 50, 90)],
+        "us_per_step_hip_graph": None if graph_us is None else round(graph_us, 2),
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 5),
         "host_wall_ms_per_step": round(wall * 1e3 / steps, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -253,8 +301,10 @@ def main():
         "config": {
             "workload": "%s: B=%d, prefix=%d, tree nodes=%d, Hq/Hkv/D=%d/%d/%d, layers=%d, paged KV block 16"
                         % (w.name, w.B, w.P, w.K, w.Hq, w.Hkv, w.D, w.layers),
-            "step": "graft_retrieve + graft_build_tree_mask + %d x graft_tree_attn + graft_accept(target_ids)" % w.layers,
+            "step": "graft_retrieve + graft_build_tree_mask + %d x graft_tree_attn + graft_accept(%s)"
+                    % (w.layers, "logits" if args.logits else "target_ids"),
             "kv_buffers_rotated": n_kv, "context_len": w.L, "vocab": w.vocab,
+            "accept_mode": "logits" if args.logits else "target_ids",
             "attention_bytes_per_layer": att_bytes, "attention_flops_per_layer": att_flops,
         },
         "per_call_us": {k: round(v, 2) for k, v in per_call_us.items()},

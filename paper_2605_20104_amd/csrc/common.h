@@ -22,19 +22,39 @@ inline int32_t check_launch() {
 
 using u64 = unsigned long long;
 
-__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int lane_mask) {
-    unsigned lo = static_cast<unsigned>(v), hi = static_cast<unsigned>(v >> 32);
-    lo = __shfl_xor(lo, lane_mask);
-    hi = __shfl_xor(hi, lane_mask);
-    return (static_cast<u64>(hi) << 32) | lo;
+// v from the lane that the DPP control names (0xB1: lane ^ 1, 0x4E: lane ^ 2, 0x141: mirror
+// within 8 lanes, 0x140: mirror within 16 lanes), both halves of the 64-bit value.
+template <int DPP_CTRL>
+__device__ __forceinline__ u64 dpp_u64(u64 v) {
+    const int lo = static_cast<int>(static_cast<unsigned>(v)), hi = static_cast<int>(static_cast<unsigned>(v >> 32));
+    const unsigned lo2 = static_cast<unsigned>(__builtin_amdgcn_update_dpp(lo, lo, DPP_CTRL, 0xf, 0xf, false));
+    const unsigned hi2 = static_cast<unsigned>(__builtin_amdgcn_update_dpp(hi, hi, DPP_CTRL, 0xf, 0xf, false));
+    return (static_cast<u64>(hi2) << 32) | lo2;
 }
 
-// Maximum of a 64-bit key over one 64-lane wavefront (all lanes get it).
+// Maximum of a 64-bit key over one 64-lane wavefront (all lanes get it).  Four DPP steps
+// reduce each row of 16 lanes (register-to-register, no LDS crossbar); the gfx950 lane
+// swaps then combine the rows: permlane16_swap(x, x) returns {rows 0,0,2,2} and
+// {rows 1,1,3,3} of x, permlane32_swap(x, x) returns {low half twice} and {high half twice}.
 __device__ __forceinline__ u64 wave_max_u64(u64 v) {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) {
-        u64 o = shfl_xor_u64(v, s);
-        v = o > v ? o : v;
+    u64 o;
+    o = dpp_u64<0xB1>(v);  v = o > v ? o : v;
+    o = dpp_u64<0x4E>(v);  v = o > v ? o : v;
+    o = dpp_u64<0x141>(v); v = o > v ? o : v;
+    o = dpp_u64<0x140>(v); v = o > v ? o : v;
+    {
+        const unsigned lo = static_cast<unsigned>(v), hi = static_cast<unsigned>(v >> 32);
+        const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        const u64 a = (static_cast<u64>(rh[0]) << 32) | rl[0], b = (static_cast<u64>(rh[1]) << 32) | rl[1];
+        v = a > b ? a : b;
+    }
+    {
+        const unsigned lo = static_cast<unsigned>(v), hi = static_cast<unsigned>(v >> 32);
+        const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        const u64 a = (static_cast<u64>(rh[0]) << 32) | rl[0], b = (static_cast<u64>(rh[1]) << 32) | rl[1];
+        v = a > b ? a : b;
     }
     return v;
 }
