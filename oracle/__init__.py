@@ -139,3 +139,53 @@ def accept(parent, tokens, n_nodes, depth_cap: int, target_ids=None, logits=None
                           depth_cap, _p(out["accept_len"]), _p(out["best_node"]), _p(out["path"]),
                           _p(out["out_tokens"]), _p(out["status"]))
     return out
+
+
+def matrix_retrieve(M, tpl_parent, tpl_rank, n_ret, tokens, parent, n_nodes):
+    """Template fill by matrix lookups, appended to the draft nodes (see oracle_matrix_retrieve).
+
+    Returns copies: tokens, parent [B,K_max], n_nodes [B], status [B].
+    """
+    M = _i32(M)
+    V, k = M.shape
+    tpl_parent, tpl_rank = _i32(tpl_parent), _i32(tpl_rank)
+    tokens, parent, n_nodes, n_ret = _i32(tokens).copy(), _i32(parent).copy(), _i32(n_nodes).copy(), _i32(n_ret)
+    B, K_max = tokens.shape
+    status = np.zeros(B, np.int32)
+    _load().oracle_matrix_retrieve(_p(M), V, k, _p(tpl_parent), _p(tpl_rank), tpl_parent.shape[0], _p(n_ret),
+                                   B, K_max, _p(tokens), _p(parent), _p(n_nodes), _p(status))
+    return {"tokens": tokens, "parent": parent, "n_nodes": n_nodes, "status": status}
+
+
+def matrix_update(M, tokens, n_nodes, logits):
+    """M[x_i] <- ids of the k largest logits of node i (see oracle_matrix_update).  Returns M', target_ids."""
+    M = _i32(M).copy()
+    V, k = M.shape
+    tokens, n_nodes = _i32(tokens), _i32(n_nodes)
+    B, K_max = tokens.shape
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    assert logits.shape == (B, K_max, V)
+    tids = np.zeros((B, K_max), np.int32)
+    _load().oracle_matrix_update(_p(tokens), _p(n_nodes), _p(logits), V, B, K_max, _p(M), k, _p(tids))
+    return {"M": M, "target_ids": tids}
+
+
+def kv_compact(k_cache, v_cache, dtype: str, layer_stride: int, n_layers: int, strides, block_table,
+               prefix_len, path, accept_len, K_max: int, Hkv: int, D: int, page_size: int = 16):
+    """Moves the accepted path's keys/values behind the prefix (see oracle_kv_compact).
+
+    Caches: flat arrays (float32, or uint16 storage bits for 'bf16'); copies are returned.
+    """
+    want = np.float32 if dtype == "f32" else np.uint16
+    k_cache, v_cache = (np.ascontiguousarray(a, dtype=want).copy() for a in (k_cache, v_cache))
+    block_table, prefix_len, path, accept_len = _i32(block_table), _i32(prefix_len), _i32(path), _i32(accept_len)
+    B, width = path.shape
+    new_len, status = np.zeros(B, np.int32), np.zeros(B, np.int32)
+    f = _load().oracle_kv_compact
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                  ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32,
+                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 2
+    f(_p(k_cache), _p(v_cache), 0 if dtype == "f32" else 1, int(layer_stride), n_layers,
+      int(strides["page"]), int(strides["token"]), int(strides["head"]), _p(block_table), block_table.shape[1],
+      page_size, _p(prefix_len), _p(path), _p(accept_len), B, width - 1, K_max, Hkv, D, _p(new_len), _p(status))
+    return {"k_cache": k_cache, "v_cache": v_cache, "new_prefix_len": new_len, "status": status}

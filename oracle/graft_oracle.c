@@ -7,7 +7,7 @@
  * with the HIP sources and must never be called from the product path; only
  * the tests, the smoke check and the benchmark's cpu_baseline leg use it.
  *
- * Each of the four functions is an exact definition (no approximation), so
+ * Each function is an exact definition (no approximation), so
  * each is written as that definition, in fp64 where floating point appears:
  *
  *   oracle_retrieve         suffix n-gram lookup over the context buffer: the
@@ -27,11 +27,24 @@
  *   oracle_accept           greedy form of the unchanged acceptance rule
  *                           (Sec. 3.3; Sec. 4 "greedy decoding"; App. B.4).
  *
+ *   oracle_matrix_retrieve  the method's own retrieval: a static template over
+ *                           successor ranks filled by lookups in the transition
+ *                           matrix and appended to the retained draft nodes
+ *                           (Sec. 3.2; App. A.1; App. A Alg. 2).
+ *   oracle_matrix_update    refresh of the matrix rows of all verified nodes
+ *                           from the target logits (Sec. 3.3 last equation).
+ *   oracle_kv_compact       cache update after acceptance (App. A Alg. 1).
+ *
  * Pins (tests/test_oracle_*.py): brute force in pure Python on tiny inputs,
  * planted-span closed forms, chain/star closed forms, comparison with a
  * library causal-attention routine on chain trees, masked-softmax
  * reformulation, losslessness against plain greedy decoding of a toy target,
- * monotonicity (App. B.1 Prop. 1, B.2 Prop. 2).  No function is unpinned.
+ * monotonicity (App. B.1 Prop. 1, B.2 Prop. 2); for the last three: hand-worked
+ * fixtures, enumeration of rank paths under an explicit successor function,
+ * a library stable sort, the gather definition on a snapshot, and equality of
+ * the accepted leaf's attention before and after the cache update.  No function
+ * is unpinned.  (The rank paths of the retrieval templates themselves are an
+ * input: the paper prints only their per-depth counts, which are pinned.)
  *
  * Build: gcc -O2 -fopenmp -shared -fPIC graft_oracle.c -o libgraft_oracle.so -lm
  */
@@ -323,5 +336,164 @@ void oracle_accept(const int32_t* parent, const int32_t* tokens, const int32_t* 
         ot[dp[best]] = ts[best];
         free(ok);
         free(dp);
+    }
+}
+
+/* ================================================================== */
+/* Steps around the verification pass (the method's own retrieval, the */
+/* matrix refresh, the cache update).  Same rules as above: plain       */
+/* definitions, test infrastructure only.                               */
+/* ================================================================== */
+
+/* ------------------------------------------------------------------ */
+/* retrieval from the transition matrix                                */
+/* ------------------------------------------------------------------ */
+/*
+ * The retrieval branch of the method (Sec. 3.2 "Stage-adaptive retrieval
+ * templates", equation x_u = M[x_F(u), r_u]; App. A.1 "Retrieval Template
+ * Details"; App. A Alg. 2 "Traverse the cached retrieval template from root
+ * x_t by matrix lookup" and "Append K_ret retrieved nodes to the retained
+ * draft nodes").
+ *
+ * M is the matrix of successor ids, int32 [V][k].  The template has N nodes;
+ * node u has parent tpl_parent[u] (an earlier template node, or -1 for the
+ * root of the tree) and successor rank tpl_rank[u].  For sequence b the first
+ * n_ret[b] template nodes are taken (a stage's template is a prefix of the
+ * envelope), filled in order, and appended behind the n_nodes[b] retained
+ * draft nodes: merged node n_nodes[b] + u gets token x_u and parent
+ * (tpl_parent[u] < 0 ? 0 : n_nodes[b] + tpl_parent[u]); n_nodes[b] grows by
+ * n_ret[b].  The root token is tokens[b][0].  A lookup from a token outside
+ * [0, V) or of an empty matrix entry (-1) gives -1, and so do all of its
+ * descendants (such a node stays in the tree and can never be accepted).
+ * n_ret[b] outside [0, N], a tree that would exceed K_max, or n_nodes[b] < 1
+ * set ST_BAD_LENGTH and leave the sequence as it was.
+ */
+void oracle_matrix_retrieve(const int32_t* M, int32_t V, int32_t k,
+                            const int32_t* tpl_parent, const int32_t* tpl_rank, int32_t N,
+                            const int32_t* n_ret, int32_t B, int32_t K_max,
+                            int32_t* tokens, int32_t* parent, int32_t* n_nodes, int32_t* status) {
+    int32_t* x = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t* tok = tokens + (size_t)b * K_max;
+        int32_t* par = parent + (size_t)b * K_max;
+        int32_t nd = n_nodes[b], nr = n_ret[b];
+        status[b] = 0;
+        if (nd < 1 || nr < 0 || nr > N || nd + nr > K_max) { status[b] = ST_BAD_LENGTH; continue; }
+        for (int32_t u = 0; u < nr; ++u) {
+            int32_t f = tpl_parent[u];
+            int32_t from = f < 0 ? tok[0] : x[f];
+            int32_t r = tpl_rank[u];
+            x[u] = (from >= 0 && from < V && r >= 0 && r < k) ? M[(size_t)from * k + r] : -1;
+            tok[nd + u] = x[u];
+            par[nd + u] = f < 0 ? 0 : nd + f;
+        }
+        n_nodes[b] = nd + nr;
+    }
+    free(x);
+}
+
+/* ------------------------------------------------------------------ */
+/* refresh of the transition matrix                                    */
+/* ------------------------------------------------------------------ */
+/*
+ * M[x_i] <- argtop-k(p_{i+1}) over every verified node, accepted or rejected
+ * (Sec. 3.3 "Warm-up and online update", last equation; App. A equation
+ * "adj_update"; App. A Alg. 1 "Update M using target logits from all verified
+ * tree nodes").  The ranking of the softmax distribution is the ranking of the
+ * logits, so no softmax is taken.
+ *
+ * For b = 0..B-1 and i = 0..n_nodes[b]-1 in this order: row tokens[b][i] of M
+ * becomes the k ids with the largest logits[b][i][.], largest first, equal
+ * logits in order of id.  Nodes are processed in order, so when a token occurs
+ * at several nodes the last one (largest b, then largest i) stays.  Tokens
+ * outside [0, V) are skipped.  target_ids[b][i] = the first of the k ids (the
+ * greedy token that the acceptance step uses), -1 for i >= n_nodes[b].
+ */
+void oracle_matrix_update(const int32_t* tokens, const int32_t* n_nodes, const float* logits, int32_t V,
+                          int32_t B, int32_t K_max, int32_t* M, int32_t k, int32_t* target_ids) {
+    int32_t* best = (int32_t*)malloc(sizeof(int32_t) * (size_t)k);
+    for (int32_t b = 0; b < B; ++b) {
+        for (int32_t i = 0; i < K_max; ++i) {
+            target_ids[(size_t)b * K_max + i] = -1;
+            if (i >= n_nodes[b]) continue;
+            const float* row = logits + ((size_t)b * K_max + i) * V;
+            /* k rounds of "largest not yet taken" */
+            for (int32_t j = 0; j < k; ++j) {
+                int32_t arg = -1;
+                for (int32_t v = 0; v < V; ++v) {
+                    int taken = 0;
+                    for (int32_t t = 0; t < j; ++t) if (best[t] == v) taken = 1;
+                    if (taken) continue;
+                    if (arg < 0 || row[v] > row[arg]) arg = v;
+                }
+                best[j] = arg;                 /* -1 only when k > V */
+            }
+            target_ids[(size_t)b * K_max + i] = best[0];
+            int32_t x = tokens[(size_t)b * K_max + i];
+            if (x < 0 || x >= V) continue;
+            for (int32_t j = 0; j < k; ++j) M[(size_t)x * k + j] = best[j];
+        }
+    }
+    free(best);
+}
+
+/* ------------------------------------------------------------------ */
+/* cache update after acceptance                                       */
+/* ------------------------------------------------------------------ */
+/*
+ * "Append accepted tokens and update target KV cache" (App. A Alg. 1; the
+ * "KV/Input Update" column of the runtime table, App. D).  During verification
+ * tree node j has its key and value at logical position P + j.  Afterwards the
+ * cache must hold the accepted path as an ordinary prefix: for k = 1 ..
+ * accept_len, position P + k takes the key and value rows (all KV heads) of
+ * position P + path[k]; path[0] = 0 is the root, already in place.  Done out
+ * of place here: all rows are read before any is written.  The new prefix
+ * length is P + accept_len + 1 (root and accepted nodes; the bonus token has
+ * no key yet).  The caches of n_layers layers lie layer_stride elements apart.
+ *
+ * path must start at 0 and increase strictly with path[k] < K_max, else the
+ * sequence is left untouched with ST_BAD_TREE; P < 0, accept_len outside
+ * [0, depth_cap] or a position beyond the block table give ST_BAD_LENGTH.
+ */
+void oracle_kv_compact(void* k_cache, void* v_cache, int32_t dtype, int64_t layer_stride, int32_t n_layers,
+                       int64_t page_stride, int64_t token_stride, int64_t head_stride,
+                       const int32_t* block_table, int32_t max_pages, int32_t page_size,
+                       const int32_t* prefix_len, const int32_t* path, const int32_t* accept_len,
+                       int32_t B, int32_t depth_cap, int32_t K_max, int32_t Hkv, int32_t D,
+                       int32_t* new_prefix_len, int32_t* status) {
+    const size_t es = dtype == DT_F32 ? 4 : 2;
+    const size_t row = (size_t)D * es;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t P = prefix_len[b], a = accept_len[b];
+        const int32_t* pth = path + (size_t)b * (depth_cap + 1);
+        const int32_t* table = block_table + (size_t)b * max_pages;
+        status[b] = 0;
+        new_prefix_len[b] = P;
+        if (P < 0 || a < 0 || a > depth_cap) { status[b] = ST_BAD_LENGTH; continue; }
+        int ok = pth[0] == 0;
+        for (int32_t k = 1; k <= a && ok; ++k) ok = pth[k] > pth[k - 1] && pth[k] < K_max;
+        if (!ok) { status[b] = ST_BAD_TREE; continue; }
+        if (a > 0 && (int64_t)P + pth[a] >= (int64_t)max_pages * page_size) { status[b] = ST_BAD_LENGTH; continue; }
+        new_prefix_len[b] = P + a + 1;
+        if (a == 0) continue;
+        unsigned char* tmp = (unsigned char*)malloc((size_t)a * Hkv * row);
+        for (int32_t l = 0; l < n_layers; ++l) {
+            for (int side = 0; side < 2; ++side) {
+                unsigned char* base = (unsigned char*)(side ? v_cache : k_cache) + (size_t)l * layer_stride * es;
+                for (int32_t k = 1; k <= a; ++k) {                        /* read everything ... */
+                    int32_t t = P + pth[k];
+                    int64_t off = (int64_t)table[t / page_size] * page_stride + (int64_t)(t % page_size) * token_stride;
+                    for (int32_t g = 0; g < Hkv; ++g)
+                        memcpy(tmp + ((size_t)(k - 1) * Hkv + g) * row, base + (off + g * head_stride) * es, row);
+                }
+                for (int32_t k = 1; k <= a; ++k) {                        /* ... then write */
+                    int32_t t = P + k;
+                    int64_t off = (int64_t)table[t / page_size] * page_stride + (int64_t)(t % page_size) * token_stride;
+                    for (int32_t g = 0; g < Hkv; ++g)
+                        memcpy(base + (off + g * head_stride) * es, tmp + ((size_t)(k - 1) * Hkv + g) * row, row);
+                }
+            }
+        }
+        free(tmp);
     }
 }
