@@ -11,6 +11,13 @@
  *     graft_tree_attn        tree-masked GQA attention over a paged KV cache (per layer)
  *     graft_accept           greedy acceptance walk
  *
+ * and the steps on either side of it in the decoding loop (App. A, Alg. 1 and 2):
+ *
+ *     graft_matrix_retrieve  the method's retrieval: a rank template filled by lookups
+ *                            in the GPU-resident transition matrix, appended to the tree
+ *     graft_matrix_update    refresh of the matrix rows from the verification logits
+ *     graft_kv_compact       cache update: the accepted path becomes an ordinary prefix
+ *
  * Conventions shared by every call
  *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
  *    never allocates, frees or keeps them.  Scratch memory comes from
@@ -47,6 +54,7 @@ extern "C" {
 #define GRAFT_MAX_NGRAM   32    /* n_max: longest suffix matched                    */
 #define GRAFT_PAGE_SIZE   16    /* tokens per KV page                               */
 #define GRAFT_ARGMAX_CHUNKS 16  /* vocabulary chunks per logits row in graft_accept */
+#define GRAFT_MAX_SUCCESSORS 16 /* k: successors per row of the transition matrix   */
 
 /* return codes */
 #define GRAFT_OK             0
@@ -225,6 +233,91 @@ int32_t graft_accept(const int32_t* parent, const int32_t* tokens, const int32_t
                      int32_t B, int32_t K_max, int32_t depth_cap,
                      int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* out_tokens,
                      int32_t* status, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * graft_matrix_retrieve - the retrieval branch of the method (Sec. 3.2, "GPU-resident
+ * adjacency matrix" and "Stage-adaptive retrieval templates": x_u = M[x_F(u), r_u];
+ * App. A.1; App. A Alg. 2 "Traverse the cached retrieval template from root x_t by
+ * matrix lookup" and "Append K_ret retrieved nodes to the retained draft nodes").
+ *
+ *     M          [V,k]  int32 successor ids, -1 = empty entry (read only)
+ *     tpl_parent [N]    parent template node of node u, -1 = the tree's root; < u
+ *     tpl_rank   [N]    successor rank r_u, 0 <= r_u < k
+ *     n_ret      [B]    template nodes to take for sequence b (a stage's template is a
+ *                       prefix of the envelope), 0 <= n_ret[b] <= N
+ *     tokens, parent [B,K_max], n_nodes [B]   IN/OUT: the retained draft nodes on entry
+ *                       (root = tokens[b,0]); node n_nodes[b] + u receives token x_u and
+ *                       parent (tpl_parent[u] < 0 ? 0 : n_nodes[b] + tpl_parent[u]);
+ *                       n_nodes[b] grows by n_ret[b].  Entries past the new end are not
+ *                       touched.
+ * A lookup from a token outside [0,V) or of an empty entry gives -1, and so do all
+ * descendants (such nodes stay in the tree; they can never be accepted).
+ * status [B]: GRAFT_STATUS_BAD_LENGTH if n_nodes[b] < 1, n_ret[b] outside [0,N] or the
+ * tree would exceed K_max; GRAFT_STATUS_BAD_TREE if one of the first n_ret[b] template
+ * nodes breaks the rules above.  In both cases the sequence is left as it was.
+ *
+ * 1 <= N <= GRAFT_MAX_NODES, 1 <= k <= GRAFT_MAX_SUCCESSORS, V >= 1, K_max <= GRAFT_MAX_NODES.
+ */
+int32_t graft_matrix_retrieve(const int32_t* M, int32_t V, int32_t k,
+                              const int32_t* tpl_parent, const int32_t* tpl_rank, int32_t N,
+                              const int32_t* n_ret, int32_t B, int32_t K_max,
+                              int32_t* tokens, int32_t* parent, int32_t* n_nodes, int32_t* status,
+                              void* stream);
+
+/*
+ * graft_matrix_update - M[x_i] <- argtop-k(p_{i+1}) for every verified node, accepted
+ * or rejected (Sec. 3.3 "Warm-up and online update", last equation; App. A equation
+ * "adj_update"; App. A Alg. 1 "Update M using target logits from all verified tree
+ * nodes").  The order of the probabilities is the order of the logits: no softmax.
+ *
+ *     tokens [B,K_max], n_nodes [B]   the verified tree
+ *     logits [B,K_max,V] fp32         target logits per node (inputs assumed NaN-free)
+ *     M      [V,k] int32              IN/OUT: row tokens[b,i] becomes the k ids with the
+ *                                     largest logits of node i, largest first, equal
+ *                                     logits in order of id (-0.0 equals +0.0)
+ *     target_ids [B,K_max]            OUT: the first of the k ids (the greedy token that
+ *                                     graft_accept takes as input), -1 for padding nodes
+ * Where a token occurs at several nodes the node with the largest (b, i) decides its
+ * row; tokens outside [0,V) are skipped.  The same scan of the logits serves the
+ * acceptance step: call graft_accept with this target_ids.
+ *
+ * 1 <= k <= GRAFT_MAX_SUCCESSORS, k <= V, B * K_max <= 65536,
+ * workspace >= graft_matrix_update_workspace_bytes(B,K_max,V,k), 8-byte aligned.
+ */
+size_t graft_matrix_update_workspace_bytes(int32_t B, int32_t K_max, int32_t V, int32_t k);
+
+int32_t graft_matrix_update(const int32_t* tokens, const int32_t* n_nodes, const float* logits, int32_t V,
+                            int32_t B, int32_t K_max, int32_t* M, int32_t k, int32_t* target_ids,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * graft_kv_compact - "Append accepted tokens and update target KV cache" (App. A
+ * Alg. 1; the "KV/Input Update" column of the runtime table in App. D).  During
+ * verification tree node j has its key and value at logical position P + j.  For
+ * k = 1 .. accept_len[b], position P + k takes the key and value rows (all KV heads)
+ * of position P + path[b,k]; path[b,0] = 0 is the root and stays.  Every row is read
+ * before any row of the same sequence and layer is written.
+ *
+ *     k_cache, v_cache   paged caches as in graft_tree_attn (IN/OUT); layer l of
+ *                        n_layers starts layer_stride elements after layer l - 1
+ *     block_table [B,max_pages], prefix_len [B]
+ *     path [B,depth_cap+1], accept_len [B]   as written by graft_accept
+ *     new_prefix_len [B] OUT: prefix_len + accept_len + 1 (root and accepted nodes; the
+ *                        bonus token has no key yet)
+ * status [B]: GRAFT_STATUS_BAD_TREE if path does not start at 0, does not increase
+ * strictly or reaches K_max; GRAFT_STATUS_BAD_LENGTH if prefix_len < 0, accept_len
+ * outside [0,depth_cap] or a position lies beyond the block table.  Then nothing of
+ * that sequence is moved and new_prefix_len = prefix_len.
+ *
+ * dtype GRAFT_F32 or GRAFT_BF16 (element size only), D in {64,128}, strides as in
+ * graft_tree_attn, 0 <= depth_cap < GRAFT_MAX_NODES, 1 <= n_layers <= 65535.
+ */
+int32_t graft_kv_compact(void* k_cache, void* v_cache, int64_t layer_stride, int32_t n_layers,
+                         int64_t page_stride, int64_t token_stride, int64_t head_stride,
+                         const int32_t* block_table, int32_t max_pages,
+                         const int32_t* prefix_len, const int32_t* path, const int32_t* accept_len,
+                         int32_t B, int32_t depth_cap, int32_t K_max, int32_t Hkv, int32_t D, int32_t dtype,
+                         int32_t* new_prefix_len, int32_t* status, void* stream);
 
 #ifdef __cplusplus
 }

@@ -366,7 +366,9 @@ void oracle_accept(const int32_t* parent, const int32_t* tokens, const int32_t* 
  * [0, V) or of an empty matrix entry (-1) gives -1, and so do all of its
  * descendants (such a node stays in the tree and can never be accepted).
  * n_ret[b] outside [0, N], a tree that would exceed K_max, or n_nodes[b] < 1
- * set ST_BAD_LENGTH and leave the sequence as it was.
+ * set ST_BAD_LENGTH; a template node (among the first n_ret[b]) whose parent
+ * is not an earlier node or -1, or whose rank is outside [0, k), sets
+ * ST_BAD_TREE.  Either way the sequence is left as it was.
  */
 void oracle_matrix_retrieve(const int32_t* M, int32_t V, int32_t k,
                             const int32_t* tpl_parent, const int32_t* tpl_rank, int32_t N,
@@ -379,11 +381,15 @@ void oracle_matrix_retrieve(const int32_t* M, int32_t V, int32_t k,
         int32_t nd = n_nodes[b], nr = n_ret[b];
         status[b] = 0;
         if (nd < 1 || nr < 0 || nr > N || nd + nr > K_max) { status[b] = ST_BAD_LENGTH; continue; }
+        int ok = 1;
+        for (int32_t u = 0; u < nr; ++u)
+            if (tpl_parent[u] < -1 || tpl_parent[u] >= u || tpl_rank[u] < 0 || tpl_rank[u] >= k) ok = 0;
+        if (!ok) { status[b] = ST_BAD_TREE; continue; }
         for (int32_t u = 0; u < nr; ++u) {
             int32_t f = tpl_parent[u];
             int32_t from = f < 0 ? tok[0] : x[f];
             int32_t r = tpl_rank[u];
-            x[u] = (from >= 0 && from < V && r >= 0 && r < k) ? M[(size_t)from * k + r] : -1;
+            x[u] = (from >= 0 && from < V) ? M[(size_t)from * k + r] : -1;
             tok[nd + u] = x[u];
             par[nd + u] = f < 0 ? 0 : nd + f;
         }

@@ -21,6 +21,7 @@ GRAFT_MASK_WORDS = 2
 GRAFT_MAX_CHAINS = 8
 GRAFT_MAX_NGRAM = 32
 GRAFT_PAGE_SIZE = 16
+GRAFT_MAX_SUCCESSORS = 16
 GRAFT_OK, GRAFT_ERR_NULL, GRAFT_ERR_SHAPE, GRAFT_ERR_DTYPE, GRAFT_ERR_WORKSPACE, GRAFT_ERR_HIP = range(6)
 GRAFT_STATUS_BAD_LENGTH, GRAFT_STATUS_BAD_TREE, GRAFT_STATUS_PATH_OVERFLOW = 1, 2, 4
 GRAFT_F32, GRAFT_BF16 = 0, 1
@@ -42,6 +43,11 @@ _SIGNATURES = {
     "graft_accept_workspace_bytes": (_sz, [_i32] * 3),
     "graft_accept": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32,
                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "graft_matrix_retrieve": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
+    "graft_matrix_update_workspace_bytes": (_sz, [_i32] * 4),
+    "graft_matrix_update": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
+    "graft_kv_compact": (_i32, [_vp, _vp, _i64, _i32, _i64, _i64, _i64, _vp, _i32, _vp, _vp, _vp,
+                                _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
 }
 EXPORTED_SYMBOLS = tuple(_SIGNATURES)
 
@@ -200,4 +206,58 @@ def graft_accept(parent, tokens, n_nodes, depth_cap: int, target_ids=None, logit
         _ptr(out["accept_len"]), _ptr(out["best_node"]), _ptr(out["path"]), _ptr(out["out_tokens"]),
         _ptr(out["status"]), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream))
     _check("graft_accept", rc)
+    return out
+
+
+def graft_matrix_retrieve(M, tpl_parent, tpl_rank, n_ret, tokens, parent, n_nodes, status=None, stream=None):
+    """Fills the first n_ret[b] template nodes by lookups in M [V,k] and appends them to the tree
+    (tokens, parent [B,K_max] and n_nodes [B] are updated in place).  Returns status [B]."""
+    V, k = M.shape
+    B, K_max = tokens.shape
+    if status is None:
+        status = torch.empty(B, dtype=torch.int32, device=tokens.device)
+    rc = load_library().graft_matrix_retrieve(
+        _ptr(M), V, k, _ptr(tpl_parent), _ptr(tpl_rank), tpl_parent.shape[0], _ptr(n_ret), B, K_max,
+        _ptr(tokens), _ptr(parent), _ptr(n_nodes), _ptr(status), _stream(stream))
+    _check("graft_matrix_retrieve", rc)
+    return status
+
+
+def graft_matrix_update_workspace_bytes(B: int, K_max: int, V: int, k: int) -> int:
+    return int(load_library().graft_matrix_update_workspace_bytes(B, K_max, V, k))
+
+
+def graft_matrix_update(tokens, n_nodes, logits, M, target_ids=None, workspace=None, stream=None):
+    """M[tokens[b,i]] <- ids of the k largest logits of node i (M [V,k] updated in place).
+    Returns target_ids [B,K_max] (the greedy token per node)."""
+    B, K_max, V = logits.shape
+    k = M.shape[1]
+    if target_ids is None:
+        target_ids = torch.empty((B, K_max), dtype=torch.int32, device=logits.device)
+    if workspace is None:
+        workspace = torch.empty(max(graft_matrix_update_workspace_bytes(B, K_max, V, k), 8), dtype=torch.uint8,
+                                device=logits.device)
+    rc = load_library().graft_matrix_update(
+        _ptr(tokens), _ptr(n_nodes), _ptr(logits), V, B, K_max, _ptr(M), k, _ptr(target_ids),
+        _ptr(workspace), workspace.numel(), _stream(stream))
+    _check("graft_matrix_update", rc)
+    return target_ids
+
+
+def graft_kv_compact(k_cache, v_cache, layer_stride: int, n_layers: int, strides, block_table, prefix_len,
+                     path, accept_len, K_max: int, Hkv: int, D: int, out=None, stream=None):
+    """Moves the accepted path's keys/values behind the prefix in place (all n_layers layers).
+    Returns dict(new_prefix_len [B], status [B])."""
+    B, width = path.shape
+    dtype = GRAFT_F32 if k_cache.dtype == torch.float32 else GRAFT_BF16
+    assert k_cache.dtype in (torch.float32, torch.bfloat16) and v_cache.dtype == k_cache.dtype
+    if out is None:
+        out = {"new_prefix_len": torch.empty(B, dtype=torch.int32, device=path.device),
+               "status": torch.empty(B, dtype=torch.int32, device=path.device)}
+    rc = load_library().graft_kv_compact(
+        _ptr(k_cache), _ptr(v_cache), int(layer_stride), n_layers, int(strides["page"]), int(strides["token"]),
+        int(strides["head"]), _ptr(block_table), block_table.shape[1], _ptr(prefix_len), _ptr(path),
+        _ptr(accept_len), B, width - 1, K_max, Hkv, D, dtype, _ptr(out["new_prefix_len"]), _ptr(out["status"]),
+        _stream(stream))
+    _check("graft_kv_compact", rc)
     return out

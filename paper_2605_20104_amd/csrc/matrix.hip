@@ -1,0 +1,249 @@
+// graft_matrix_retrieve and graft_matrix_update: the transition matrix M[V][k] of successor
+// ids that the method keeps in GPU memory.
+//
+// Retrieval is a gather along a static template: one 128-thread workgroup per sequence, one
+// thread per template node.  A node can be filled once its parent's token is known, so the
+// template is filled in rounds, one per depth: every round is one dependent lookup in M, and
+// the nodes of a depth are looked up together.  The call is bound by those dependent
+// round trips (nine for the paper's templates), not by bandwidth.
+//
+// The refresh ranks every verified node's logits row.  Like the argmax of the acceptance
+// step it is one HBM scan of the logits (4 V bytes per node): GRAFT_ARGMAX_CHUNKS workgroups
+// per row, each thread keeps the k best keys it has seen in registers, the workgroup merges
+// them in k rounds and writes its chunk's k best to the workspace.  A key packs (logit,
+// id) into 64 bits so that "larger logit first, then smaller id" is one unsigned compare.
+// A one-wavefront kernel per node then merges the chunks, writes the greedy token and, if
+// no later node carries the same token, the matrix row.
+#include "common.h"
+
+namespace graft {
+
+constexpr int MR_THREADS = GRAFT_MAX_NODES;
+constexpr int MU_THREADS = 256;
+constexpr int MU_WAVES = MU_THREADS / 64;
+
+__global__ __launch_bounds__(MR_THREADS) void matrix_retrieve_kernel(
+    const int32_t* __restrict__ M, int32_t V, int32_t k, const int32_t* __restrict__ tpl_parent,
+    const int32_t* __restrict__ tpl_rank, int32_t N, const int32_t* __restrict__ n_ret, int32_t K_max,
+    int32_t* __restrict__ tokens, int32_t* __restrict__ parent, int32_t* __restrict__ n_nodes,
+    int32_t* __restrict__ status) {
+    const int b = blockIdx.x, u = threadIdx.x;
+    __shared__ int32_t x[GRAFT_MAX_NODES];        // token of template node u
+    __shared__ int32_t done[GRAFT_MAX_NODES];
+    int32_t* tok = tokens + static_cast<size_t>(b) * K_max;
+    int32_t* par = parent + static_cast<size_t>(b) * K_max;
+    const int32_t nd = n_nodes[b], nr = n_ret[b];
+    if (nd < 1 || nr < 0 || nr > N || nd + nr > K_max) {       // uniform over the workgroup
+        if (u == 0) status[b] = GRAFT_STATUS_BAD_LENGTH;
+        return;
+    }
+    const bool mine = u < nr;
+    const int32_t f = mine ? tpl_parent[u] : -1;
+    const int32_t r = mine ? tpl_rank[u] : 0;
+    const int bad = mine && (f < -1 || f >= u || r < 0 || r >= k);
+    if (__syncthreads_or(bad)) {
+        if (u == 0) status[b] = GRAFT_STATUS_BAD_TREE;
+        return;
+    }
+    const int32_t root = tok[0];
+    done[u] = 0;
+    __syncthreads();
+    // rounds: a node is filled in the round after its parent's (at most nr rounds; the
+    // workgroup stops as soon as every node is filled)
+    bool filled = !mine;
+    for (int round = 0; round < nr; ++round) {
+        const bool ready = !filled && (f < 0 || done[f] != 0);
+        int32_t from = 0;
+        if (ready) from = f < 0 ? root : x[f];
+        __syncthreads();                            // all reads of done/x of this round before its writes
+        if (ready) {
+            const int32_t v = (from >= 0 && from < V) ? M[static_cast<size_t>(from) * k + r] : -1;
+            x[u] = v;
+            done[u] = 1;
+            tok[nd + u] = v;
+            par[nd + u] = f < 0 ? 0 : nd + f;
+            filled = true;
+        }
+        if (__syncthreads_and(filled)) break;
+    }
+    if (u == 0) {
+        n_nodes[b] = nd + nr;
+        status[b] = 0;
+    }
+}
+
+// ---- refresh ------------------------------------------------------------------------------
+
+// (logit, id) -> key: larger logit = larger key; among equal logits the smaller id is larger.
+__device__ __forceinline__ u64 rank_key(float v, int32_t id) {
+    v += 0.0f;                                      // -0.0 -> +0.0: they compare equal
+    const unsigned bits = __float_as_uint(v);
+    const unsigned ord = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+    return (static_cast<u64>(ord) << 32) | static_cast<u64>(0xffffffffu - static_cast<unsigned>(id));
+}
+__device__ __forceinline__ int32_t key_id(u64 key) {
+    return static_cast<int32_t>(0xffffffffu - static_cast<unsigned>(key & 0xffffffffu));
+}
+
+template <int KK>
+__device__ __forceinline__ void topk_insert(u64 (&top)[KK], u64 key) {
+    if (key > top[KK - 1]) {
+#pragma unroll
+        for (int j = 0; j < KK; ++j) {
+            if (key > top[j]) { const u64 t = top[j]; top[j] = key; key = t; }
+        }
+    }
+}
+
+// Chunk scan: workgroup (chunk, node, sequence) -> its chunk's k best keys, best first.
+template <int KK>
+__global__ __launch_bounds__(MU_THREADS) void topk_chunk_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ n_nodes, int32_t K_max, int32_t V,
+    int32_t k, u64* __restrict__ partial) {
+    const int chunk = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    u64* out = partial + ((static_cast<size_t>(b) * K_max + i) * GRAFT_ARGMAX_CHUNKS + chunk) * k;
+    const int32_t n = n_nodes[b];
+    if (i >= n || n > K_max) {                      // padding node
+        if (tid < k) out[tid] = 0;
+        return;
+    }
+    const int32_t quads = (V + 3) / 4;
+    const int32_t per = (quads + GRAFT_ARGMAX_CHUNKS - 1) / GRAFT_ARGMAX_CHUNKS;
+    const int32_t q0 = chunk * per;
+    const int32_t q1 = (q0 + per) < quads ? (q0 + per) : quads;
+    const float* row = logits + (static_cast<size_t>(b) * K_max + i) * V;
+    u64 top[KK];
+#pragma unroll
+    for (int j = 0; j < KK; ++j) top[j] = 0;
+    if (V % 4 == 0) {                               // every row start is 16-byte aligned
+        const float4* row4 = reinterpret_cast<const float4*>(row);
+        for (int32_t qd = q0 + tid; qd < q1; qd += 2 * MU_THREADS) {
+            const int32_t qe = qd + MU_THREADS;
+            const float4 xa = row4[qd];
+            const float4 xb = qe < q1 ? row4[qe] : float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            topk_insert<KK>(top, rank_key(xa.x, qd * 4));
+            topk_insert<KK>(top, rank_key(xa.y, qd * 4 + 1));
+            topk_insert<KK>(top, rank_key(xa.z, qd * 4 + 2));
+            topk_insert<KK>(top, rank_key(xa.w, qd * 4 + 3));
+            if (qe < q1) {
+                topk_insert<KK>(top, rank_key(xb.x, qe * 4));
+                topk_insert<KK>(top, rank_key(xb.y, qe * 4 + 1));
+                topk_insert<KK>(top, rank_key(xb.z, qe * 4 + 2));
+                topk_insert<KK>(top, rank_key(xb.w, qe * 4 + 3));
+            }
+        }
+    } else {
+        const int32_t e0 = q0 * 4, e1 = (q1 * 4) < V ? (q1 * 4) : V;
+        for (int32_t e = e0 + tid; e < e1; e += MU_THREADS) topk_insert<KK>(top, rank_key(row[e], e));
+    }
+    // k rounds: every wavefront offers its best remaining key, the owner of the round's
+    // winner (keys are unique: the id is part of them) pops it
+    __shared__ u64 red[2][MU_WAVES];
+    for (int j = 0; j < k; ++j) {
+        const u64 wmax = wave_max_u64(top[0]);
+        if (lane == 0) red[j & 1][wave] = wmax;
+        __syncthreads();
+        u64 gmax = red[j & 1][0];
+#pragma unroll
+        for (int w = 1; w < MU_WAVES; ++w) gmax = red[j & 1][w] > gmax ? red[j & 1][w] : gmax;
+        if (tid == 0) out[j] = gmax;
+        if (gmax != 0 && top[0] == gmax) {
+#pragma unroll
+            for (int t = 0; t + 1 < KK; ++t) top[t] = top[t + 1];
+            top[KK - 1] = 0;
+        }
+    }
+}
+
+// One wavefront per node: merge the chunks' keys, write the greedy token and the matrix row.
+__global__ __launch_bounds__(64) void matrix_update_merge_kernel(
+    const int32_t* __restrict__ tokens, const int32_t* __restrict__ n_nodes, int32_t V, int32_t B,
+    int32_t K_max, int32_t k, const u64* __restrict__ partial, int32_t* __restrict__ M,
+    int32_t* __restrict__ target_ids) {
+    const int node = blockIdx.x;                    // b * K_max + i
+    const int b = node / K_max, i = node - b * K_max;
+    const int lane = threadIdx.x;
+    const int32_t n = n_nodes[b];
+    if (i >= n || n > K_max) {
+        if (lane == 0) target_ids[node] = -1;
+        return;
+    }
+    // GRAFT_ARGMAX_CHUNKS * k <= 256 candidates: four per lane, kept sorted
+    const u64* cand = partial + static_cast<size_t>(node) * GRAFT_ARGMAX_CHUNKS * k;
+    const int n_cand = GRAFT_ARGMAX_CHUNKS * k;
+    u64 c[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) c[t] = (lane + 64 * t) < n_cand ? cand[lane + 64 * t] : 0;
+#pragma unroll
+    for (int a = 0; a < 3; ++a)
+#pragma unroll
+        for (int t = 0; t + 1 < 4 - a; ++t)
+            if (c[t + 1] > c[t]) { const u64 s = c[t]; c[t] = c[t + 1]; c[t + 1] = s; }
+    // is this the last node (largest b, then i) carrying its token?
+    const int32_t x = tokens[node];
+    bool later = false;
+    const int total = B * K_max;
+    for (int o = node + 1 + lane; o < total; o += 64) {
+        const int ob = o / K_max, oi = o - ob * K_max;
+        const int32_t on = n_nodes[ob];
+        if (oi < on && on <= K_max && tokens[o] == x) later = true;
+    }
+    const bool write_row = x >= 0 && x < V && __builtin_amdgcn_ballot_w64(later) == 0;
+    for (int j = 0; j < k; ++j) {
+        const u64 gmax = wave_max_u64(c[0]);
+        if (lane == 0) {
+            const int32_t id = gmax != 0 ? key_id(gmax) : -1;
+            if (j == 0) target_ids[node] = id;
+            if (write_row) M[static_cast<size_t>(x) * k + j] = id;
+        }
+        if (gmax != 0 && c[0] == gmax) { c[0] = c[1]; c[1] = c[2]; c[2] = c[3]; c[3] = 0; }
+    }
+}
+
+}  // namespace graft
+
+extern "C" int32_t graft_matrix_retrieve(const int32_t* M, int32_t V, int32_t k,
+                                         const int32_t* tpl_parent, const int32_t* tpl_rank, int32_t N,
+                                         const int32_t* n_ret, int32_t B, int32_t K_max,
+                                         int32_t* tokens, int32_t* parent, int32_t* n_nodes, int32_t* status,
+                                         void* stream) {
+    if (!M || !tpl_parent || !tpl_rank || !n_ret || !tokens || !parent || !n_nodes || !status) return GRAFT_ERR_NULL;
+    if (V < 1 || k < 1 || k > GRAFT_MAX_SUCCESSORS || N < 1 || N > GRAFT_MAX_NODES || B < 1 || K_max < 1 ||
+        K_max > GRAFT_MAX_NODES)
+        return GRAFT_ERR_SHAPE;
+    hipLaunchKernelGGL(graft::matrix_retrieve_kernel, dim3(B), dim3(graft::MR_THREADS), 0,
+                       static_cast<hipStream_t>(stream), M, V, k, tpl_parent, tpl_rank, N, n_ret, K_max,
+                       tokens, parent, n_nodes, status);
+    return graft::check_launch();
+}
+
+extern "C" size_t graft_matrix_update_workspace_bytes(int32_t B, int32_t K_max, int32_t V, int32_t k) {
+    if (B < 1 || K_max < 1 || K_max > GRAFT_MAX_NODES || V < 1 || k < 1 || k > GRAFT_MAX_SUCCESSORS) return 0;
+    return static_cast<size_t>(B) * K_max * GRAFT_ARGMAX_CHUNKS * k * sizeof(unsigned long long);
+}
+
+extern "C" int32_t graft_matrix_update(const int32_t* tokens, const int32_t* n_nodes, const float* logits,
+                                       int32_t V, int32_t B, int32_t K_max, int32_t* M, int32_t k,
+                                       int32_t* target_ids, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+    using namespace graft;
+    if (!tokens || !n_nodes || !logits || !M || !target_ids) return GRAFT_ERR_NULL;
+    if (B < 1 || B > 65535 || K_max < 1 || K_max > GRAFT_MAX_NODES || V < 1 || k < 1 ||
+        k > GRAFT_MAX_SUCCESSORS || k > V || static_cast<int64_t>(B) * K_max > 65536)
+        return GRAFT_ERR_SHAPE;
+    const size_t need = graft_matrix_update_workspace_bytes(B, K_max, V, k);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<size_t>(workspace) & 7) != 0)
+        return GRAFT_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    u64* partial = static_cast<u64*>(workspace);
+    dim3 grid(GRAFT_ARGMAX_CHUNKS, K_max, B);
+    if (k <= 4) hipLaunchKernelGGL(topk_chunk_kernel<4>, grid, dim3(MU_THREADS), 0, s, logits, n_nodes, K_max, V, k, partial);
+    else if (k <= 8) hipLaunchKernelGGL(topk_chunk_kernel<8>, grid, dim3(MU_THREADS), 0, s, logits, n_nodes, K_max, V, k, partial);
+    else hipLaunchKernelGGL(topk_chunk_kernel<16>, grid, dim3(MU_THREADS), 0, s, logits, n_nodes, K_max, V, k, partial);
+    int32_t rc = check_launch();
+    if (rc != GRAFT_OK) return rc;
+    hipLaunchKernelGGL(matrix_update_merge_kernel, dim3(B * K_max), dim3(64), 0, s, tokens, n_nodes, V, B, K_max, k,
+                       partial, M, target_ids);
+    return check_launch();
+}

@@ -38,7 +38,7 @@ def test_header_constants_match_binding():
     import paper_2605_20104_amd as g
     text = open(HEADER).read()
     for name in ("GRAFT_MAX_NODES", "GRAFT_MASK_WORDS", "GRAFT_MAX_CHAINS", "GRAFT_MAX_NGRAM",
-                 "GRAFT_PAGE_SIZE", "GRAFT_ERR_NULL", "GRAFT_ERR_SHAPE", "GRAFT_ERR_DTYPE",
+                 "GRAFT_PAGE_SIZE", "GRAFT_MAX_SUCCESSORS", "GRAFT_ERR_NULL", "GRAFT_ERR_SHAPE", "GRAFT_ERR_DTYPE",
                  "GRAFT_ERR_WORKSPACE", "GRAFT_ERR_HIP", "GRAFT_STATUS_BAD_LENGTH", "GRAFT_STATUS_BAD_TREE",
                  "GRAFT_STATUS_PATH_OVERFLOW", "GRAFT_F32", "GRAFT_BF16"):
         m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
@@ -140,6 +140,63 @@ def test_accept_validation(lib):
     assert call(a3=P, a4=1000) == g.GRAFT_ERR_WORKSPACE   # logits mode needs the workspace
     assert call(a3=P, a4=1000, a14=P, a15=8) == g.GRAFT_ERR_WORKSPACE
     assert lib.graft_accept_workspace_bytes(1, 16, 1000) == 16 * 16 * 8
+
+
+def _caller(f, ok):
+    def call(**kw):
+        a = list(ok)
+        for k, v in kw.items():
+            a[int(k[1:])] = v
+        return f(*a)
+    return call
+
+
+def test_matrix_retrieve_validation(lib):
+    import paper_2605_20104_amd as g
+    call = _caller(lib.graft_matrix_retrieve, [P, 1000, 8, P, P, 80, P, 2, 64, P, P, P, P, None])
+    for i in (0, 3, 4, 6, 9, 10, 11, 12):
+        assert call(**{"a%d" % i: None}) == g.GRAFT_ERR_NULL
+    assert call(a1=0) == g.GRAFT_ERR_SHAPE
+    assert call(a2=0) == g.GRAFT_ERR_SHAPE
+    assert call(a2=g.GRAFT_MAX_SUCCESSORS + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a5=0) == g.GRAFT_ERR_SHAPE
+    assert call(a5=g.GRAFT_MAX_NODES + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a7=0) == g.GRAFT_ERR_SHAPE
+    assert call(a8=g.GRAFT_MAX_NODES + 1) == g.GRAFT_ERR_SHAPE
+
+
+def test_matrix_update_validation_and_workspace(lib):
+    import paper_2605_20104_amd as g
+    call = _caller(lib.graft_matrix_update, [P, P, P, 1000, 2, 16, P, 8, P, 0x2000, 1 << 30, None])
+    for i in (0, 1, 2, 6, 8):
+        assert call(**{"a%d" % i: None}) == g.GRAFT_ERR_NULL
+    assert call(a3=0) == g.GRAFT_ERR_SHAPE
+    assert call(a7=0) == g.GRAFT_ERR_SHAPE
+    assert call(a7=g.GRAFT_MAX_SUCCESSORS + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a3=4, a7=8) == g.GRAFT_ERR_SHAPE                  # k > V
+    assert call(a4=1024, a5=128) == g.GRAFT_ERR_SHAPE             # B * K_max > 65536
+    assert call(a9=None) == g.GRAFT_ERR_WORKSPACE
+    assert call(a10=8) == g.GRAFT_ERR_WORKSPACE
+    assert call(a9=0x2004) == g.GRAFT_ERR_WORKSPACE               # not 8-byte aligned
+    assert lib.graft_matrix_update_workspace_bytes(2, 16, 1000, 8) == 2 * 16 * 16 * 8 * 8
+    assert lib.graft_matrix_update_workspace_bytes(2, 16, 1000, 0) == 0
+
+
+def test_kv_compact_validation(lib):
+    import paper_2605_20104_amd as g
+    ok = [P, P, 1 << 20, 4, 8 * 16 * 128, 128, 16 * 128, P, 130, P, P, P, 2, 16, 64, 8, 128, g.GRAFT_BF16, P, P, None]
+    call = _caller(lib.graft_kv_compact, ok)
+    for i in (0, 1, 7, 9, 10, 11, 18, 19):
+        assert call(**{"a%d" % i: None}) == g.GRAFT_ERR_NULL
+    assert call(a17=9) == g.GRAFT_ERR_DTYPE
+    assert call(a3=0) == g.GRAFT_ERR_SHAPE                        # n_layers
+    assert call(a2=0) == g.GRAFT_ERR_SHAPE                        # several layers need a stride
+    assert call(a5=100) == g.GRAFT_ERR_SHAPE                      # token stride < D
+    assert call(a5=132) == g.GRAFT_ERR_SHAPE                      # 16-byte columns must stay aligned
+    assert call(a16=96) == g.GRAFT_ERR_SHAPE                      # D
+    assert call(a13=g.GRAFT_MAX_NODES) == g.GRAFT_ERR_SHAPE       # depth_cap
+    assert call(a14=0) == g.GRAFT_ERR_SHAPE                       # K_max
+    assert call(a0=0x1008) == g.GRAFT_ERR_SHAPE                   # cache base not 16-byte aligned
 
 
 def test_binding_has_no_fallback(monkeypatch):

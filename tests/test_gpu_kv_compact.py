@@ -1,0 +1,103 @@
+"""GPU parity of graft_kv_compact against the CPU oracle (bit-exact: it only moves bytes)."""
+import numpy as np
+import pytest
+import torch
+
+import inputs
+import oracle
+import paper_2605_20104_amd as graft
+from gpu_util import dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed, dtype, B, Hkv, D, n_layers, P, K, depth_cap, token_major):
+    rng = np.random.default_rng(seed)
+    max_pages = (max(P) + K + 15) // 16
+    n_pages = B * max_pages + 3
+    table = rng.permutation(n_pages)[: B * max_pages].reshape(B, max_pages).astype(np.int32)
+    if token_major:
+        strides = {"page": 16 * Hkv * D, "token": Hkv * D, "head": D}
+    else:
+        strides = {"page": Hkv * 16 * D, "token": D, "head": 16 * D}
+    layer_stride = n_pages * Hkv * 16 * D
+    n = n_layers * layer_stride
+    if dtype == "f32":
+        k, v = rng.standard_normal(n).astype(np.float32), rng.standard_normal(n).astype(np.float32)
+    else:
+        k, v = rng.integers(0, 1 << 16, n).astype(np.uint16), rng.integers(0, 1 << 16, n).astype(np.uint16)
+    path = np.full((B, depth_cap + 1), -1, np.int32)
+    acc = np.zeros(B, np.int32)
+    for b in range(B):
+        a = int(rng.integers(0, min(depth_cap, K - 1) + 1))
+        path[b, 0] = 0
+        path[b, 1:a + 1] = np.sort(rng.choice(np.arange(1, K), size=a, replace=False))
+        acc[b] = a
+    return dict(k=k, v=v, table=table, strides=strides, layer_stride=layer_stride, n_layers=n_layers,
+                P=np.array(P, np.int32), path=path, acc=acc, K=K, Hkv=Hkv, D=D, B=B, dtype=dtype)
+
+
+def _both(c):
+    ref = oracle.kv_compact(c["k"], c["v"], c["dtype"], c["layer_stride"], c["n_layers"], c["strides"], c["table"],
+                            c["P"], c["path"], c["acc"], c["K"], c["Hkv"], c["D"])
+    kind = "f32" if c["dtype"] == "f32" else "bf16"
+    kd, vd = dev(c["k"], kind), dev(c["v"], kind)
+    out = graft.graft_kv_compact(kd, vd, c["layer_stride"], c["n_layers"], c["strides"], dev(c["table"]),
+                                 dev(c["P"]), dev(c["path"]), dev(c["acc"]), c["K"], c["Hkv"], c["D"])
+    torch.cuda.synchronize()
+    assert (host(out["status"]) == ref["status"]).all()
+    assert (host(out["new_prefix_len"]) == ref["new_prefix_len"]).all()
+    as_bits = (lambda t: t.cpu().numpy()) if c["dtype"] == "f32" else (lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16))
+    assert (as_bits(kd) == ref["k_cache"]).all() and (as_bits(vd) == ref["v_cache"]).all()
+    return ref
+
+
+@pytest.mark.parametrize("seed,dtype,B,Hkv,D,n_layers,P,K,depth_cap,token_major", [
+    (0, "f32", 1, 2, 64, 1, (256,), 16, 8, False),
+    (1, "bf16", 3, 8, 128, 4, (5, 300, 17), 64, 16, False),
+    (2, "bf16", 2, 4, 128, 3, (1000, 33), 48, 12, True),
+    (3, "f32", 2, 3, 128, 2, (0, 15), 96, 40, True),
+    (4, "bf16", 4, 8, 64, 2, (31, 32, 47, 48), 128, 127, False),
+])
+def test_compact_matches_oracle(seed, dtype, B, Hkv, D, n_layers, P, K, depth_cap, token_major):
+    _both(_case(seed, dtype, B, Hkv, D, n_layers, P, K, depth_cap, token_major))
+
+
+def test_compact_long_and_adversarial_paths():
+    c = _case(5, "bf16", 3, 8, 128, 2, (100, 7, 64), 128, 127, False)
+    c["path"][0, :] = np.arange(128)                       # the whole chain: nothing moves
+    c["acc"][0] = 127
+    c["path"][1, :64] = np.arange(64) * 2                  # every destination is an earlier batch's source region
+    c["acc"][1] = 63
+    c["path"][2, :20] = [0] + list(range(109, 128))        # far sources, 19 rows (three batches)
+    c["acc"][2] = 19
+    _both(c)
+
+
+def test_compact_error_paths():
+    c = _case(6, "f32", 4, 2, 64, 2, (9, 9, 9, 9), 24, 8, False)
+    c["path"][0, :3], c["acc"][0] = [0, 5, 5], 2
+    c["path"][1, :3], c["acc"][1] = [1, 2, 3], 2
+    c["path"][2, :3], c["acc"][2] = [0, 3, 24], 2
+    c["acc"][3] = 9
+    ref = _both(c)
+    assert ref["status"].tolist() == [graft.GRAFT_STATUS_BAD_TREE] * 3 + [graft.GRAFT_STATUS_BAD_LENGTH]
+    c["P"][:] = [-1, 9, 9, 9]
+    c["acc"][:] = [0, -1, 0, 0]
+    ref = _both(c)
+    assert ref["status"].tolist() == [graft.GRAFT_STATUS_BAD_LENGTH] * 2 + [0, 0]
+
+
+def test_compact_after_a_real_step():
+    """accept -> compact on workload c2's shapes, all 32 layers in one call, checked against the oracle."""
+    w = inputs.get_workload("c2")
+    s = inputs.make_step_inputs(w)
+    att = inputs.make_attention_inputs(w, kv_buffers=2, q_layers=1)
+    a = oracle.accept(s["parent"], s["tokens"], s["n_nodes"], 16, target_ids=s["target_ids"])
+    k = np.concatenate([x.reshape(-1) for x in att["k_cache"]])
+    v = np.concatenate([x.reshape(-1) for x in att["v_cache"]])
+    c = dict(k=k, v=v, table=att["block_table"], strides=att["strides"], layer_stride=att["k_cache"][0].size,
+             n_layers=2, P=s["prefix_len"], path=a["path"], acc=a["accept_len"], K=w.K, Hkv=w.Hkv, D=w.D,
+             B=w.B, dtype="bf16")
+    ref = _both(c)
+    assert ref["status"].tolist() == [0] and ref["new_prefix_len"][0] == w.P + a["accept_len"][0] + 1

@@ -126,6 +126,12 @@ def test_retrieve_rejects_what_does_not_fit():
     r = oracle.matrix_retrieve(M, [-1, 0, 1], [0, 0, 0], [3, 4, 2], tokens, parent, [4, 1, 0])
     assert r["status"].tolist() == [oracle.ST_BAD_LENGTH] * 3            # 4+3 > 6; 4 > N; no root
     assert r["n_nodes"].tolist() == [4, 1, 0] and (r["tokens"] == 0).all()
+    # ill-formed templates: a parent that is not an earlier node, a rank outside [0, k)
+    tokens = np.zeros((2, 6), np.int32)
+    for tp, tr in (([-1, 1, 0], [0, 0, 0]), ([-1, 0, 1], [0, 2, 0]), ([-2, 0, 1], [0, 0, 0])):
+        r = oracle.matrix_retrieve(M, tp, tr, [3, 1], tokens, np.full((2, 6), -1, np.int32), [1, 1])
+        assert r["status"].tolist() == [oracle.ST_BAD_TREE, oracle.ST_BAD_TREE if tp[0] < -1 else 0]
+        assert r["n_nodes"].tolist() == [1, 1 if tp[0] < -1 else 2]
 
 
 # ---------------------------------------------------------------- refresh of the matrix
