@@ -79,6 +79,10 @@ def main():
                     help="reuse one KV buffer for every layer (Infinity-Cache-resident figure for small workloads)")
     ap.add_argument("--logits", action="store_true",
                     help="graft_accept takes fp32 logits [B,K,V] (argmax scan on the GPU) instead of target ids")
+    ap.add_argument("--extended", action="store_true",
+                    help="also time the steps around verification (matrix retrieval, matrix refresh from the "
+                         "logits, cache update after acceptance) and report them in extra keys; the timed step "
+                         "and the headline metric stay the same")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run five plain 1 GiB -> 1 GiB elementwise copies and exit: the reference that the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
@@ -246,6 +250,55 @@ def main():
         "accept": time_call(accept),
     }
 
+    # ---- optional: the steps around verification, each timed on its own (medians)
+    extended = None
+    if args.extended:
+        from inputs import templates
+        tp, tr, _, sizes = templates.retrieval_envelope()
+        kk = 8
+        rng = np.random.default_rng(inputs.generate.BASE_SEED + 77)
+        M = torch.from_numpy(rng.integers(0, w.vocab, (w.vocab, kk), dtype=np.int32)).cuda()
+        tpl_p, tpl_r = up(tp), up(tr)
+        n_ret = up(np.full(B, sizes["d5"], np.int32))
+        n_draft = max(1, min(K - sizes["d5"], K // 2))
+        tok2, par2 = d["tokens"].clone(), d["parent"].clone()
+        nn2 = torch.full((B,), n_draft, dtype=torch.int32, device=dev)
+        st2 = torch.empty(B, dtype=torch.int32, device=dev)
+
+        def matrix_retrieve():
+            nn2.fill_(n_draft)
+            graft.graft_matrix_retrieve(M, tpl_p, tpl_r, n_ret, tok2, par2, nn2, status=st2)
+
+        lg = logits if logits is not None else torch.from_numpy(
+            inputs.make_step_inputs(w, with_logits=True)["logits"]).cuda()
+        mu_ws = torch.empty(graft.graft_matrix_update_workspace_bytes(B, K, w.vocab, kk), dtype=torch.uint8, device=dev)
+        ids2 = torch.empty((B, K), dtype=torch.int32, device=dev)
+
+        def matrix_update():
+            graft.graft_matrix_update(d["tokens"], d["n_nodes"], lg, M, target_ids=ids2, workspace=mu_ws)
+
+        n_l = min(w.layers, n_kv)
+        kv_all_k = torch.cat([x.reshape(-1) for x in kc[:n_l]])
+        kv_all_v = torch.cat([x.reshape(-1) for x in vc[:n_l]])
+        kc_out = {"new_prefix_len": torch.empty(B, dtype=torch.int32, device=dev),
+                  "status": torch.empty(B, dtype=torch.int32, device=dev)}
+
+        def kv_compact():
+            graft.graft_kv_compact(kv_all_k, kv_all_v, kc[0].numel(), n_l, att["strides"], table, d["prefix_len"],
+                                   acc_out["path"], acc_out["accept_len"], K, w.Hkv, w.D, out=kc_out)
+
+        t_mr, t_mu, t_kc = time_call(matrix_retrieve), time_call(matrix_update), time_call(kv_compact)
+        torch.cuda.synchronize()
+        assert torch.equal(ids2, d["target_ids"]) and int(st2.max()) == 0 and int(kc_out["status"].max()) == 0
+        scan_bytes = 4.0 * B * K * w.vocab
+        extended = {
+            "matrix_retrieve_us": round(t_mr, 2), "template_nodes": int(sizes["d5"]),
+            "matrix_update_us": round(t_mu, 2), "matrix_update_logits_bytes": int(scan_bytes), "successors_k": kk,
+            "matrix_update_GBps_incl_launch": round(scan_bytes / (t_mu * 1e-6) / 1e9, 1),
+            "kv_compact_us": round(t_kc, 2), "kv_compact_layers": n_l,
+            "kv_compact_accept_len": [int(x) for x in acc_out["accept_len"].cpu().numpy()],
+        }
+
     # ---- optional: the same step replayed from a captured HIP graph (launch overhead removed)
     graph_us = None
     if args.graph:
@@ -308,6 +361,7 @@ def main():
             "attention_bytes_per_layer": att_bytes, "attention_flops_per_layer": att_flops,
         },
         "per_call_us": {k: round(v, 2) for k, v in per_call_us.items()},
+        "extended": extended,
         "roofline": {
             "kernel": "tree_attn_mfma_kernel" if (w.dtype == "bf16" and w.D == 128) else "tree_attn_simple_kernel",
             "bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",

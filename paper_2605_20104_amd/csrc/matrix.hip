@@ -85,17 +85,90 @@ __device__ __forceinline__ int32_t key_id(u64 key) {
     return static_cast<int32_t>(0xffffffffu - static_cast<unsigned>(key & 0xffffffffu));
 }
 
+// The thread's KK best keys, best first.  Almost every element fails the first test (one
+// float compare against the value of the worst kept key; equal values go on to the exact
+// 64-bit compare because the id decides then).
 template <int KK>
-__device__ __forceinline__ void topk_insert(u64 (&top)[KK], u64 key) {
-    if (key > top[KK - 1]) {
+__device__ __forceinline__ void topk_insert(u64 (&top)[KK], float& worst, float v, int32_t id) {
+    if (v >= worst) {
+        u64 key = rank_key(v, id);
+        if (key > top[KK - 1]) {
 #pragma unroll
-        for (int j = 0; j < KK; ++j) {
-            if (key > top[j]) { const u64 t = top[j]; top[j] = key; key = t; }
+            for (int j = 0; j < KK; ++j) {
+                if (key > top[j]) { const u64 t = top[j]; top[j] = key; key = t; }
+            }
+            // value of the new worst key (-inf while fewer than KK have been seen)
+            const unsigned ord = static_cast<unsigned>(top[KK - 1] >> 32);
+            const unsigned bits = (ord & 0x80000000u) ? (ord & 0x7fffffffu) : ~ord;
+            worst = top[KK - 1] == 0 ? -INFINITY : __uint_as_float(bits);
         }
     }
 }
 
+// The scan of one thread's share of a chunk.  take(value, id) is called for every element in
+// order of id.
+template <class Take>
+__device__ __forceinline__ void scan_chunk(const float* __restrict__ row, int32_t V, int32_t q0, int32_t q1,
+                                           int tid, Take&& take) {
+    if (V % 4 == 0) {                               // every row start is 16-byte aligned
+        const float4* row4 = reinterpret_cast<const float4*>(row);
+        constexpr int U = 4;                        // 16-byte loads in flight per thread
+        for (int32_t qd = q0 + tid; qd < q1; qd += U * MU_THREADS) {
+            float4 x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int32_t qu = qd + u * MU_THREADS;
+                x[u] = row4[qu < q1 ? qu : qd];     // a lane past the end re-reads its first quad (skipped below)
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int32_t qu = qd + u * MU_THREADS;
+                if (qu < q1) {
+                    take(x[u].x, qu * 4);
+                    take(x[u].y, qu * 4 + 1);
+                    take(x[u].z, qu * 4 + 2);
+                    take(x[u].w, qu * 4 + 3);
+                }
+            }
+        }
+    } else {
+        const int32_t e0 = q0 * 4, e1 = (q1 * 4) < V ? (q1 * 4) : V;
+        for (int32_t e = e0 + tid; e < e1; e += MU_THREADS) take(row[e], e);
+    }
+}
+
+// k rounds over the workgroup: every wavefront offers its best remaining key, the owner of
+// the round's winner (keys are unique: the id is part of them) pops it.  Returns how many of
+// this thread's keys were taken.
+template <int KK>
+__device__ __forceinline__ int select_rounds(u64 (&top)[KK], int k, u64 (&red)[2][MU_WAVES], u64* out,
+                                             int tid, int lane, int wave) {
+    int taken = 0;
+    for (int j = 0; j < k; ++j) {
+        const u64 wmax = wave_max_u64(top[0]);
+        if (lane == 0) red[j & 1][wave] = wmax;
+        __syncthreads();
+        u64 gmax = red[j & 1][0];
+#pragma unroll
+        for (int w = 1; w < MU_WAVES; ++w) gmax = red[j & 1][w] > gmax ? red[j & 1][w] : gmax;
+        if (tid == 0) out[j] = gmax;
+        if (gmax != 0 && top[0] == gmax) {
+#pragma unroll
+            for (int t = 0; t + 1 < KK; ++t) top[t] = top[t + 1];
+            top[KK - 1] = 0;
+            ++taken;
+        }
+    }
+    return taken;
+}
+
 // Chunk scan: workgroup (chunk, node, sequence) -> its chunk's k best keys, best first.
+//
+// Fast path: every thread keeps only its three best elements, by value with the earlier
+// (smaller) id first among equals, in branch-free code; the k rounds then pick from those.
+// That is exact unless some thread had all three of its elements taken (it might hold a
+// fourth that belongs to the k best): then, rarely, the workgroup repeats the scan with
+// exact per-thread lists of KK >= k keys.
 template <int KK>
 __global__ __launch_bounds__(MU_THREADS) void topk_chunk_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ n_nodes, int32_t K_max, int32_t V,
@@ -113,47 +186,34 @@ __global__ __launch_bounds__(MU_THREADS) void topk_chunk_kernel(
     const int32_t q0 = chunk * per;
     const int32_t q1 = (q0 + per) < quads ? (q0 + per) : quads;
     const float* row = logits + (static_cast<size_t>(b) * K_max + i) * V;
+    __shared__ u64 red[2][MU_WAVES];
+
+    float v0 = 0.f, v1 = 0.f, v2 = 0.f;
+    int32_t i0 = -1, i1 = -1, i2 = -1;              // -1: slot still empty
+    scan_chunk(row, V, q0, q1, tid, [&](float v, int32_t id) {
+        const bool c0 = (v > v0) | (i0 < 0), c1 = (v > v1) | (i1 < 0), c2 = (v > v2) | (i2 < 0);
+        v2 = c1 ? v1 : (c2 ? v : v2);
+        i2 = c1 ? i1 : (c2 ? id : i2);
+        v1 = c0 ? v0 : (c1 ? v : v1);
+        i1 = c0 ? i0 : (c1 ? id : i1);
+        v0 = c0 ? v : v0;
+        i0 = c0 ? id : i0;
+    });
+    u64 t3[3];
+    t3[0] = i0 >= 0 ? rank_key(v0, i0) : 0;
+    t3[1] = i1 >= 0 ? rank_key(v1, i1) : 0;
+    t3[2] = i2 >= 0 ? rank_key(v2, i2) : 0;
+    const int taken = select_rounds<3>(t3, k, red, out, tid, lane, wave);
+    if (k <= 3) return;
+    if (__syncthreads_or(taken == 3) == 0) return;
+
+    // exact path: per-thread sorted lists of KK keys
     u64 top[KK];
 #pragma unroll
     for (int j = 0; j < KK; ++j) top[j] = 0;
-    if (V % 4 == 0) {                               // every row start is 16-byte aligned
-        const float4* row4 = reinterpret_cast<const float4*>(row);
-        for (int32_t qd = q0 + tid; qd < q1; qd += 2 * MU_THREADS) {
-            const int32_t qe = qd + MU_THREADS;
-            const float4 xa = row4[qd];
-            const float4 xb = qe < q1 ? row4[qe] : float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-            topk_insert<KK>(top, rank_key(xa.x, qd * 4));
-            topk_insert<KK>(top, rank_key(xa.y, qd * 4 + 1));
-            topk_insert<KK>(top, rank_key(xa.z, qd * 4 + 2));
-            topk_insert<KK>(top, rank_key(xa.w, qd * 4 + 3));
-            if (qe < q1) {
-                topk_insert<KK>(top, rank_key(xb.x, qe * 4));
-                topk_insert<KK>(top, rank_key(xb.y, qe * 4 + 1));
-                topk_insert<KK>(top, rank_key(xb.z, qe * 4 + 2));
-                topk_insert<KK>(top, rank_key(xb.w, qe * 4 + 3));
-            }
-        }
-    } else {
-        const int32_t e0 = q0 * 4, e1 = (q1 * 4) < V ? (q1 * 4) : V;
-        for (int32_t e = e0 + tid; e < e1; e += MU_THREADS) topk_insert<KK>(top, rank_key(row[e], e));
-    }
-    // k rounds: every wavefront offers its best remaining key, the owner of the round's
-    // winner (keys are unique: the id is part of them) pops it
-    __shared__ u64 red[2][MU_WAVES];
-    for (int j = 0; j < k; ++j) {
-        const u64 wmax = wave_max_u64(top[0]);
-        if (lane == 0) red[j & 1][wave] = wmax;
-        __syncthreads();
-        u64 gmax = red[j & 1][0];
-#pragma unroll
-        for (int w = 1; w < MU_WAVES; ++w) gmax = red[j & 1][w] > gmax ? red[j & 1][w] : gmax;
-        if (tid == 0) out[j] = gmax;
-        if (gmax != 0 && top[0] == gmax) {
-#pragma unroll
-            for (int t = 0; t + 1 < KK; ++t) top[t] = top[t + 1];
-            top[KK - 1] = 0;
-        }
-    }
+    float worst = -INFINITY;
+    scan_chunk(row, V, q0, q1, tid, [&](float v, int32_t id) { topk_insert<KK>(top, worst, v, id); });
+    select_rounds<KK>(top, k, red, out, tid, lane, wave);
 }
 
 // One wavefront per node: merge the chunks' keys, write the greedy token and the matrix row.
