@@ -189,3 +189,20 @@ def kv_compact(k_cache, v_cache, dtype: str, layer_stride: int, n_layers: int, s
       int(strides["page"]), int(strides["token"]), int(strides["head"]), _p(block_table), block_table.shape[1],
       page_size, _p(prefix_len), _p(path), _p(accept_len), B, width - 1, K_max, Hkv, D, _p(new_len), _p(status))
     return {"k_cache": k_cache, "v_cache": v_cache, "new_prefix_len": new_len, "status": status}
+
+
+def prune_select(parent, tokens, logq, n_nodes, chk_depth, chk_log_tau, chk_keep, chk_ret):
+    """Confidence gates + top-K_draft selection on a finished draft tree (see oracle_prune_select)."""
+    parent, tokens, n_nodes = _i32(parent), _i32(tokens), _i32(n_nodes)
+    logq = np.ascontiguousarray(logq, dtype=np.float32)
+    chk_depth, chk_keep, chk_ret = _i32(chk_depth), _i32(chk_keep), _i32(chk_ret)
+    chk_log_tau = np.ascontiguousarray(chk_log_tau, dtype=np.float32)
+    B, K_max = parent.shape
+    out = {"parent": np.zeros((B, K_max), np.int32), "tokens": np.zeros((B, K_max), np.int32),
+           "index": np.zeros((B, K_max), np.int32), "n_nodes": np.zeros(B, np.int32),
+           "stage": np.zeros(B, np.int32), "n_ret": np.zeros(B, np.int32), "status": np.zeros(B, np.int32)}
+    _load().oracle_prune_select(_p(parent), _p(tokens), _p(logq), _p(n_nodes), B, K_max, _p(chk_depth),
+                                _p(chk_log_tau), _p(chk_keep), _p(chk_ret), chk_depth.shape[0],
+                                _p(out["parent"]), _p(out["tokens"]), _p(out["index"]), _p(out["n_nodes"]),
+                                _p(out["stage"]), _p(out["n_ret"]), _p(out["status"]))
+    return out

@@ -34,12 +34,14 @@
  *   oracle_matrix_update    refresh of the matrix rows of all verified nodes
  *                           from the target logits (Sec. 3.3 last equation).
  *   oracle_kv_compact       cache update after acceptance (App. A Alg. 1).
+ *   oracle_prune_select     confidence gates and top-K_draft selection on a
+ *                           finished draft tree (Sec. 3.1; App. A Alg. 2; App. E).
  *
  * Pins (tests/test_oracle_*.py): brute force in pure Python on tiny inputs,
  * planted-span closed forms, chain/star closed forms, comparison with a
  * library causal-attention routine on chain trees, masked-softmax
  * reformulation, losslessness against plain greedy decoding of a toy target,
- * monotonicity (App. B.1 Prop. 1, B.2 Prop. 2); for the last three: hand-worked
+ * monotonicity (App. B.1 Prop. 1, B.2 Prop. 2); for the last four: hand-worked
  * fixtures, enumeration of rank paths under an explicit successor function,
  * a library stable sort, the gather definition on a snapshot, and equality of
  * the accepted leaf's attention before and after the cache update.  No function
@@ -502,4 +504,88 @@ void oracle_kv_compact(void* k_cache, void* v_cache, int32_t dtype, int64_t laye
         }
         free(tmp);
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* confidence gates and selection of the retained draft nodes          */
+/* ------------------------------------------------------------------ */
+/*
+ * Dynamic-depth pruning on a finished draft tree (Sec. 3.1 "Dynamic-depth
+ * pruning": cumulative path score S_{d,j} = S_{d-1,F(j)} + log q, confidence
+ * c_d = exp(max_j S_{d,j}), gate g_d = 1[c_d > tau_d]; App. A Alg. 2 "Resolve
+ * (K_draft, K_ret)" and "Keep the top K_draft draft nodes by cumulative path
+ * score"; App. E: in the batched implementation the whole static tree is built
+ * first and the gates are applied afterwards).
+ *
+ * logq[b][i] is the draft model's log-probability of node i given its parent
+ * (node 0, the root, has score 0 whatever logq[b][0] holds).  Scores are
+ * accumulated in fp32 from the root downwards, S_i = S_parent(i) + logq_i, in
+ * that order, because they decide a selection.  Checkpoint c looks at tree
+ * depth chk_depth[c]; the gate is taken in the log domain, max_j S_{d,j} >
+ * chk_log_tau[c] (the same inequality as c_d > tau_d, without rounding an
+ * exponential); a depth without nodes has confidence 0 (gate closed).  The
+ * stage is the first checkpoint whose gate is closed; it keeps the chk_keep[c]
+ * nodes with the largest scores (equal scores: smaller index first, so that a
+ * parent comes before its child) and announces chk_ret[c] retrieval slots.  If
+ * every gate is open, stage = n_chk, all nodes stay and n_ret = 0.
+ *
+ * The kept nodes are written in their old order: out_index[new] = old index,
+ * out_tokens, out_parent (re-indexed), out_n_nodes; entries past the end are
+ * -1.  An ill-formed tree, or a kept node whose parent was not kept (possible
+ * only with positive logq), gives ST_BAD_TREE with out_n_nodes = 0, stage = -1.
+ */
+void oracle_prune_select(const int32_t* parent, const int32_t* tokens, const float* logq,
+                         const int32_t* n_nodes, int32_t B, int32_t K_max,
+                         const int32_t* chk_depth, const float* chk_log_tau, const int32_t* chk_keep,
+                         const int32_t* chk_ret, int32_t n_chk,
+                         int32_t* out_parent, int32_t* out_tokens, int32_t* out_index, int32_t* out_n_nodes,
+                         int32_t* stage, int32_t* n_ret, int32_t* status) {
+    float* S = (float*)malloc(sizeof(float) * (size_t)K_max);
+    int32_t* dp = (int32_t*)malloc(sizeof(int32_t) * (size_t)K_max);
+    int32_t* newi = (int32_t*)malloc(sizeof(int32_t) * (size_t)K_max);
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t* par = parent + (size_t)b * K_max;
+        const int32_t* tok = tokens + (size_t)b * K_max;
+        const float* lq = logq + (size_t)b * K_max;
+        int32_t* op = out_parent + (size_t)b * K_max;
+        int32_t* ot = out_tokens + (size_t)b * K_max;
+        int32_t* oi = out_index + (size_t)b * K_max;
+        const int32_t n = n_nodes[b];
+        for (int32_t i = 0; i < K_max; ++i) { op[i] = -1; ot[i] = -1; oi[i] = -1; }
+        status[b] = 0; out_n_nodes[b] = 0; stage[b] = -1; n_ret[b] = 0;
+        if (!tree_ok(par, n, K_max)) { status[b] = ST_BAD_TREE; continue; }
+        S[0] = 0.0f; dp[0] = 0;
+        for (int32_t i = 1; i < n; ++i) { S[i] = S[par[i]] + lq[i]; dp[i] = dp[par[i]] + 1; }
+        int32_t st = n_chk;
+        for (int32_t c = 0; c < n_chk && st == n_chk; ++c) {
+            int open = 0;
+            for (int32_t i = 0; i < n; ++i)
+                if (dp[i] == chk_depth[c] && S[i] > chk_log_tau[c]) open = 1;
+            if (!open) st = c;
+        }
+        int32_t keep = st == n_chk ? n : chk_keep[st];
+        if (keep > n) keep = n;
+        if (keep < 1) keep = 1;
+        /* node i is kept when fewer than `keep` nodes come before it in (score, index) order */
+        int32_t cnt = 0;
+        int ok = 1;
+        for (int32_t i = 0; i < n; ++i) {
+            int32_t before = 0;
+            for (int32_t j = 0; j < n; ++j)
+                if (S[j] > S[i] || (S[j] == S[i] && j < i)) ++before;
+            newi[i] = before < keep ? cnt++ : -1;
+            if (newi[i] >= 0 && i > 0 && newi[par[i]] < 0) ok = 0;
+        }
+        if (!ok) { status[b] = ST_BAD_TREE; continue; }
+        for (int32_t i = 0; i < n; ++i) {
+            if (newi[i] < 0) continue;
+            oi[newi[i]] = i;
+            ot[newi[i]] = tok[i];
+            op[newi[i]] = i == 0 ? -1 : newi[par[i]];
+        }
+        out_n_nodes[b] = cnt;
+        stage[b] = st;
+        n_ret[b] = st == n_chk ? 0 : chk_ret[st];
+    }
+    free(S); free(dp); free(newi);
 }
