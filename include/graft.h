@@ -13,6 +13,7 @@
  *
  * and the steps on either side of it in the decoding loop (App. A, Alg. 1 and 2):
  *
+ *     graft_prune_select     confidence gates and the choice of the retained draft nodes
  *     graft_matrix_retrieve  the method's retrieval: a rank template filled by lookups
  *                            in the GPU-resident transition matrix, appended to the tree
  *     graft_matrix_update    refresh of the matrix rows from the verification logits
@@ -55,6 +56,7 @@ extern "C" {
 #define GRAFT_PAGE_SIZE   16    /* tokens per KV page                               */
 #define GRAFT_ARGMAX_CHUNKS 16  /* vocabulary chunks per logits row in graft_accept */
 #define GRAFT_MAX_SUCCESSORS 16 /* k: successors per row of the transition matrix   */
+#define GRAFT_MAX_CHECKPOINTS 16 /* pruning checkpoints per call                     */
 
 /* return codes */
 #define GRAFT_OK             0
@@ -318,6 +320,41 @@ int32_t graft_kv_compact(void* k_cache, void* v_cache, int64_t layer_stride, int
                          const int32_t* prefix_len, const int32_t* path, const int32_t* accept_len,
                          int32_t B, int32_t depth_cap, int32_t K_max, int32_t Hkv, int32_t D, int32_t dtype,
                          int32_t* new_prefix_len, int32_t* status, void* stream);
+
+/*
+ * graft_prune_select - dynamic-depth pruning applied to a finished draft tree (Sec. 3.1:
+ * cumulative path score S_{d,j} = S_{d-1,F(j)} + log q(x_{d,j} | .), confidence
+ * c_d = exp(max_j S_{d,j}), gate g_d = 1[c_d > tau_d]; App. A Alg. 2 "Resolve (K_draft,
+ * K_ret)" and "Keep the top K_draft draft nodes by cumulative path score"; App. E: the
+ * batched implementation builds the whole static tree first and gates afterwards).
+ *
+ *     parent, tokens [B,K_max], n_nodes [B]   the draft tree
+ *     logq [B,K_max] fp32   log-probability of each node given its parent, <= 0 (the
+ *                           root's entry is ignored: its score is 0)
+ *     chk_depth, chk_log_tau, chk_keep, chk_ret [n_chk]   checkpoints in the order they are
+ *                           tried: tree depth looked at, LOG of the threshold tau_d, draft
+ *                           nodes kept and retrieval slots announced when pruned there
+ * Scores are accumulated in fp32 from the root downwards.  Gate c is open when some node
+ * of depth chk_depth[c] has S > chk_log_tau[c] (the inequality c_d > tau_d taken in the
+ * log domain; a depth without nodes is closed).  stage [B] = first closed checkpoint, or
+ * n_chk when all are open (then every node is kept and n_ret = 0).  Otherwise the
+ * chk_keep[stage] nodes (at least 1, at most n_nodes) with the largest scores are kept,
+ * equal scores in index order, and n_ret [B] = chk_ret[stage].
+ *     out_index  [B,K_max]  old index of each kept node, in old order; -1 past the end
+ *     out_tokens, out_parent [B,K_max]   the kept tree, parents re-indexed; -1 past the end
+ *     out_n_nodes [B]
+ * The outputs must not overlap the inputs.  status [B]: GRAFT_STATUS_BAD_TREE for an
+ * ill-formed tree or when a kept node's parent was not kept (only possible with positive
+ * logq); then out_n_nodes = 0, stage = -1, n_ret = 0 and the output rows are -1.
+ *
+ * 0 <= n_chk <= GRAFT_MAX_CHECKPOINTS, K_max <= GRAFT_MAX_NODES.
+ */
+int32_t graft_prune_select(const int32_t* parent, const int32_t* tokens, const float* logq,
+                           const int32_t* n_nodes, int32_t B, int32_t K_max,
+                           const int32_t* chk_depth, const float* chk_log_tau, const int32_t* chk_keep,
+                           const int32_t* chk_ret, int32_t n_chk,
+                           int32_t* out_parent, int32_t* out_tokens, int32_t* out_index, int32_t* out_n_nodes,
+                           int32_t* stage, int32_t* n_ret, int32_t* status, void* stream);
 
 #ifdef __cplusplus
 }

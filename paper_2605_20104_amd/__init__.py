@@ -22,6 +22,7 @@ GRAFT_MAX_CHAINS = 8
 GRAFT_MAX_NGRAM = 32
 GRAFT_PAGE_SIZE = 16
 GRAFT_MAX_SUCCESSORS = 16
+GRAFT_MAX_CHECKPOINTS = 16
 GRAFT_OK, GRAFT_ERR_NULL, GRAFT_ERR_SHAPE, GRAFT_ERR_DTYPE, GRAFT_ERR_WORKSPACE, GRAFT_ERR_HIP = range(6)
 GRAFT_STATUS_BAD_LENGTH, GRAFT_STATUS_BAD_TREE, GRAFT_STATUS_PATH_OVERFLOW = 1, 2, 4
 GRAFT_F32, GRAFT_BF16 = 0, 1
@@ -43,6 +44,7 @@ _SIGNATURES = {
     "graft_accept_workspace_bytes": (_sz, [_i32] * 3),
     "graft_accept": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32,
                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "graft_prune_select": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32] + [_vp] * 8),
     "graft_matrix_retrieve": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
     "graft_matrix_update_workspace_bytes": (_sz, [_i32] * 4),
     "graft_matrix_update": (_i32, [_vp, _vp, _vp, _i32, _i32, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
@@ -260,4 +262,22 @@ def graft_kv_compact(k_cache, v_cache, layer_stride: int, n_layers: int, strides
         _ptr(accept_len), B, width - 1, K_max, Hkv, D, dtype, _ptr(out["new_prefix_len"]), _ptr(out["status"]),
         _stream(stream))
     _check("graft_kv_compact", rc)
+    return out
+
+
+def graft_prune_select(parent, tokens, logq, n_nodes, chk_depth, chk_log_tau, chk_keep, chk_ret, out=None,
+                       stream=None):
+    """Confidence gates + selection of the retained draft nodes.  Returns a dict of device tensors:
+    parent, tokens, index [B,K_max], n_nodes, stage, n_ret, status [B]."""
+    B, K_max = parent.shape
+    dev = parent.device
+    if out is None:
+        out = {k: torch.empty((B, K_max), dtype=torch.int32, device=dev) for k in ("parent", "tokens", "index")}
+        out.update({k: torch.empty(B, dtype=torch.int32, device=dev) for k in ("n_nodes", "stage", "n_ret", "status")})
+    rc = load_library().graft_prune_select(
+        _ptr(parent), _ptr(tokens), _ptr(logq), _ptr(n_nodes), B, K_max, _ptr(chk_depth), _ptr(chk_log_tau),
+        _ptr(chk_keep), _ptr(chk_ret), chk_depth.shape[0], _ptr(out["parent"]), _ptr(out["tokens"]),
+        _ptr(out["index"]), _ptr(out["n_nodes"]), _ptr(out["stage"]), _ptr(out["n_ret"]), _ptr(out["status"]),
+        _stream(stream))
+    _check("graft_prune_select", rc)
     return out

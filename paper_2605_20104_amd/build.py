@@ -13,7 +13,7 @@ CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libgraft.so")
-SOURCES = ["api.hip", "retrieve.hip", "tree_mask.hip", "tree_attn.hip", "accept.hip", "matrix.hip", "kv_compact.hip"]
+SOURCES = ["api.hip", "retrieve.hip", "tree_mask.hip", "tree_attn.hip", "accept.hip", "matrix.hip", "kv_compact.hip", "prune.hip"]
 
 # packed-fp32 code generation is switched off for every device compile; VGPR spills must not
 # land in AccVGPRs (the attention kernel manages those by hand)

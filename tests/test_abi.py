@@ -38,7 +38,7 @@ def test_header_constants_match_binding():
     import paper_2605_20104_amd as g
     text = open(HEADER).read()
     for name in ("GRAFT_MAX_NODES", "GRAFT_MASK_WORDS", "GRAFT_MAX_CHAINS", "GRAFT_MAX_NGRAM",
-                 "GRAFT_PAGE_SIZE", "GRAFT_MAX_SUCCESSORS", "GRAFT_ERR_NULL", "GRAFT_ERR_SHAPE", "GRAFT_ERR_DTYPE",
+                 "GRAFT_PAGE_SIZE", "GRAFT_MAX_SUCCESSORS", "GRAFT_MAX_CHECKPOINTS", "GRAFT_ERR_NULL", "GRAFT_ERR_SHAPE", "GRAFT_ERR_DTYPE",
                  "GRAFT_ERR_WORKSPACE", "GRAFT_ERR_HIP", "GRAFT_STATUS_BAD_LENGTH", "GRAFT_STATUS_BAD_TREE",
                  "GRAFT_STATUS_PATH_OVERFLOW", "GRAFT_F32", "GRAFT_BF16"):
         m = re.search(r"#define\s+%s\s+(\d+)" % name, text)
@@ -180,6 +180,17 @@ def test_matrix_update_validation_and_workspace(lib):
     assert call(a9=0x2004) == g.GRAFT_ERR_WORKSPACE               # not 8-byte aligned
     assert lib.graft_matrix_update_workspace_bytes(2, 16, 1000, 8) == 2 * 16 * 16 * 8 * 8
     assert lib.graft_matrix_update_workspace_bytes(2, 16, 1000, 0) == 0
+
+
+def test_prune_select_validation(lib):
+    import paper_2605_20104_amd as g
+    call = _caller(lib.graft_prune_select, [P, P, P, P, 2, 64, P, P, P, P, 3, P, P, P, P, P, P, P, None])
+    for i in (0, 1, 2, 3, 6, 7, 8, 9, 11, 12, 13, 14, 15, 16, 17):
+        assert call(**{"a%d" % i: None}) == g.GRAFT_ERR_NULL
+    assert call(a4=0) == g.GRAFT_ERR_SHAPE
+    assert call(a5=g.GRAFT_MAX_NODES + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a10=-1) == g.GRAFT_ERR_SHAPE
+    assert call(a10=g.GRAFT_MAX_CHECKPOINTS + 1) == g.GRAFT_ERR_SHAPE
 
 
 def test_kv_compact_validation(lib):
