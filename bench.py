@@ -287,11 +287,23 @@ def main():
             graft.graft_kv_compact(kv_all_k, kv_all_v, kc[0].numel(), n_l, att["strides"], table, d["prefix_len"],
                                    acc_out["path"], acc_out["accept_len"], K, w.Hkv, w.D, out=kc_out)
 
+        lq = torch.from_numpy(np.log(rng.random((B, K)).astype(np.float32) * 0.9 + 0.05)).cuda()
+        chk = [up(np.array(a, np.int32)) for a in ([1, 2, 6], [8, 24, 40], [52, 36, 20])]
+        chk_tau = torch.tensor([-0.5, -2.0, -6.0], dtype=torch.float32, device=dev)
+        ps_out = {k_: torch.empty((B, K), dtype=torch.int32, device=dev) for k_ in ("parent", "tokens", "index")}
+        ps_out.update({k_: torch.empty(B, dtype=torch.int32, device=dev) for k_ in ("n_nodes", "stage", "n_ret", "status")})
+
+        def prune_select():
+            graft.graft_prune_select(d["parent"], d["tokens"], lq, d["n_nodes"], chk[0], chk_tau, chk[1], chk[2],
+                                     out=ps_out)
+
+        t_ps = time_call(prune_select)
         t_mr, t_mu, t_kc = time_call(matrix_retrieve), time_call(matrix_update), time_call(kv_compact)
         torch.cuda.synchronize()
         assert torch.equal(ids2, d["target_ids"]) and int(st2.max()) == 0 and int(kc_out["status"].max()) == 0
         scan_bytes = 4.0 * B * K * w.vocab
         extended = {
+            "prune_select_us": round(t_ps, 2),
             "matrix_retrieve_us": round(t_mr, 2), "template_nodes": int(sizes["d5"]),
             "matrix_update_us": round(t_mu, 2), "matrix_update_logits_bytes": int(scan_bytes), "successors_k": kk,
             "matrix_update_GBps_incl_launch": round(scan_bytes / (t_mu * 1e-6) / 1e9, 1),
