@@ -78,6 +78,8 @@ MFMA_CASES = [
     (1, 128, 4, 2, 130),      # K = 128: both mask words
     (3, 33, 6, 2, 64),        # odd sizes, prefix exactly one stage
     (1, 20, 16, 16, 31),      # group size 1
+    (1, 128, 32, 2, 100),     # R = 2048: the largest row count, seven row tiles
+    (16, 8, 16, 8, 95),       # many sequences, few rows: one workgroup per (sequence, head)
 ]
 
 
@@ -95,6 +97,24 @@ def test_bf16_ragged_batch_and_padding_nodes():
     got, _, _ = check_case(w, seed=5, n_nodes=n_nodes, prefix=prefix)
     for b, n in enumerate(n_nodes):
         assert (got[b, n:] == 0).all()                  # padding rows are zeros
+
+
+def test_bf16_capacity_far_beyond_the_length():
+    """The launch is planned from the block table's capacity: with a table for 64K tokens and a few hundred
+    actual ones most splits have nothing to do and must contribute nothing."""
+    w = shape_workload(2, 40, 16, 4, 128, 300)
+    rng = np.random.default_rng(21)
+    att = inputs.make_attention_inputs(w, seed=21)
+    table = att["block_table"]
+    wide = np.zeros((w.B, 4096), np.int32)                      # unused entries point at page 0 (readable)
+    wide[:, :table.shape[1]] = table
+    att = dict(att, block_table=wide)
+    parent = np.stack([inputs.random_recursive_tree(rng, w.K, 8) for _ in range(w.B)])
+    n_nodes, prefix = np.array([40, 23], np.int32), np.array([300, 31], np.int32)
+    got = run_attn(att, "bf16", prefix, n_nodes, gpu_mask(parent, n_nodes, prefix), w.Hkv)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"], wide, prefix,
+                           n_nodes, parent, w.Hq, w.Hkv, w.D, 16, att["scale"])
+    assert np.abs(got - ref.astype(np.float32)).max() <= TOL_BF16
 
 
 def test_bf16_token_major_layout_and_deep_chain():
