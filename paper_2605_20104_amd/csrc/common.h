@@ -59,4 +59,28 @@ __device__ __forceinline__ u64 wave_max_u64(u64 v) {
     return v;
 }
 
+// Maximum of a float over one 64-lane wavefront (all lanes get it); same steps as above.
+template <int DPP_CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    const int b = __float_as_int(v);
+    return __int_as_float(__builtin_amdgcn_update_dpp(b, b, DPP_CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+    v = __builtin_fmaxf(v, dpp_f32<0xB1>(v));
+    v = __builtin_fmaxf(v, dpp_f32<0x4E>(v));
+    v = __builtin_fmaxf(v, dpp_f32<0x141>(v));
+    v = __builtin_fmaxf(v, dpp_f32<0x140>(v));
+    {
+        const unsigned u = __float_as_uint(v);
+        const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+        v = __builtin_fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    {
+        const unsigned u = __float_as_uint(v);
+        const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        v = __builtin_fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    return v;
+}
+
 }  // namespace graft

@@ -9,8 +9,8 @@
 //
 // The refresh ranks every verified node's logits row.  Like the argmax of the acceptance
 // step it is one HBM scan of the logits (4 V bytes per node): GRAFT_ARGMAX_CHUNKS workgroups
-// per row, each thread keeps the k best keys it has seen in registers, the workgroup merges
-// them in k rounds and writes its chunk's k best to the workspace.  A key packs (logit,
+// per row; a workgroup finds a threshold from its threads' maxima, collects the few elements
+// above it and picks its chunk's k best from those in k rounds.  A key packs (logit,
 // id) into 64 bits so that "larger logit first, then smaller id" is one unsigned compare.
 // A one-wavefront kernel per node then merges the chunks, writes the greedy token and, if
 // no later node carries the same token, the matrix row.
@@ -164,11 +164,20 @@ __device__ __forceinline__ int select_rounds(u64 (&top)[KK], int k, u64 (&red)[2
 
 // Chunk scan: workgroup (chunk, node, sequence) -> its chunk's k best keys, best first.
 //
-// Fast path: every thread keeps only its three best elements, by value with the earlier
-// (smaller) id first among equals, in branch-free code; the k rounds then pick from those.
-// That is exact unless some thread had all three of its elements taken (it might hold a
-// fourth that belongs to the k best): then, rarely, the workgroup repeats the scan with
-// exact per-thread lists of KK >= k keys.
+// Fast path (aligned rows whose chunk fits in registers, MU_REG_QUADS 16-byte loads per
+// thread, all issued before anything else):
+//   1. every thread takes the maximum of its elements (one max3 per two elements);
+//   2. every wavefront finds the k-th largest of its 64 maxima (k rounds of a float max in
+//      registers; equal maxima leave together, which only lowers the result) and T is the
+//      largest of the four: at least k elements are >= T, so every one of the chunk's k
+//      best is >= T;
+//   3. the elements >= T (normally a dozen or two) are appended to a list in LDS as keys;
+//   4. one wavefront picks the result from the list in k rounds.
+// If the list overflows (long runs of equal values) or the chunk does not fit, the
+// workgroup takes the exact streaming path: per-thread sorted lists of KK >= k keys.
+constexpr int MU_REG_QUADS = 12;                    // covers V <= 196608
+constexpr int MU_LIST = 256;                        // four candidates per lane of the last wavefront
+
 template <int KK>
 __global__ __launch_bounds__(MU_THREADS) void topk_chunk_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ n_nodes, int32_t K_max, int32_t V,
@@ -187,27 +196,72 @@ __global__ __launch_bounds__(MU_THREADS) void topk_chunk_kernel(
     const int32_t q1 = (q0 + per) < quads ? (q0 + per) : quads;
     const float* row = logits + (static_cast<size_t>(b) * K_max + i) * V;
     __shared__ u64 red[2][MU_WAVES];
+    __shared__ u64 list[MU_LIST];
+    __shared__ int32_t list_n;
 
-    float v0 = 0.f, v1 = 0.f, v2 = 0.f;
-    int32_t i0 = -1, i1 = -1, i2 = -1;              // -1: slot still empty
-    scan_chunk(row, V, q0, q1, tid, [&](float v, int32_t id) {
-        const bool c0 = (v > v0) | (i0 < 0), c1 = (v > v1) | (i1 < 0), c2 = (v > v2) | (i2 < 0);
-        v2 = c1 ? v1 : (c2 ? v : v2);
-        i2 = c1 ? i1 : (c2 ? id : i2);
-        v1 = c0 ? v0 : (c1 ? v : v1);
-        i1 = c0 ? i0 : (c1 ? id : i1);
-        v0 = c0 ? v : v0;
-        i0 = c0 ? id : i0;
-    });
-    u64 t3[3];
-    t3[0] = i0 >= 0 ? rank_key(v0, i0) : 0;
-    t3[1] = i1 >= 0 ? rank_key(v1, i1) : 0;
-    t3[2] = i2 >= 0 ? rank_key(v2, i2) : 0;
-    const int taken = select_rounds<3>(t3, k, red, out, tid, lane, wave);
-    if (k <= 3) return;
-    if (__syncthreads_or(taken == 3) == 0) return;
+    bool exact = true;
+    if (V % 4 == 0 && per <= MU_REG_QUADS * MU_THREADS) {           // uniform over the grid
+        const float4* row4 = reinterpret_cast<const float4*>(row);
+        float4 x[MU_REG_QUADS];
+#pragma unroll
+        for (int u = 0; u < MU_REG_QUADS; ++u) {
+            const int32_t qu = q0 + tid + u * MU_THREADS;
+            x[u] = qu < q1 ? row4[qu] : float4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        }
+        if (tid == 0) list_n = 0;
+        float m = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < MU_REG_QUADS; ++u)
+            m = __builtin_fmaxf(__builtin_fmaxf(__builtin_fmaxf(m, x[u].x), __builtin_fmaxf(x[u].y, x[u].z)), x[u].w);
+        // T = the largest over the wavefronts of "k-th largest of the wavefront's maxima"
+        float mm = m, tw = -INFINITY;
+        for (int j = 0; j < k; ++j) {
+            tw = wave_max_f32(mm);
+            if (mm == tw) mm = -INFINITY;
+        }
+        __shared__ float tws[MU_WAVES];
+        if (lane == 0) tws[wave] = tw;
+        __syncthreads();                                             // also orders list_n = 0 before the appends
+        const float T = __builtin_fmaxf(__builtin_fmaxf(tws[0], tws[1]), __builtin_fmaxf(tws[2], tws[3]));
+#pragma unroll
+        for (int u = 0; u < MU_REG_QUADS; ++u) {
+            const int32_t qu = q0 + tid + u * MU_THREADS;
+            if (qu < q1) {
+                const float e[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    if (e[t] >= T) {
+                        const int slot = atomicAdd(&list_n, 1);
+                        if (slot < MU_LIST) list[slot] = rank_key(e[t], qu * 4 + t);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const int32_t nl = list_n;
+        if (nl <= MU_LIST) {                                         // uniform
+            if (wave == 0) {
+                u64 c4[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) c4[t] = (lane + t * 64) < nl ? list[lane + t * 64] : 0;
+#pragma unroll
+                for (int a = 0; a < 3; ++a)
+#pragma unroll
+                    for (int t = 0; t + 1 < 4 - a; ++t)
+                        if (c4[t + 1] > c4[t]) { const u64 sw = c4[t]; c4[t] = c4[t + 1]; c4[t + 1] = sw; }
+                for (int j = 0; j < k; ++j) {
+                    const u64 gmax = wave_max_u64(c4[0]);
+                    if (lane == 0) out[j] = gmax;
+                    if (gmax != 0 && c4[0] == gmax) { c4[0] = c4[1]; c4[1] = c4[2]; c4[2] = c4[3]; c4[3] = 0; }
+                }
+            }
+            exact = false;
+        }
+        __syncthreads();
+    }
+    if (!exact) return;
 
-    // exact path: per-thread sorted lists of KK keys
+    // exact streaming path: per-thread sorted lists of KK keys
     u64 top[KK];
 #pragma unroll
     for (int j = 0; j < KK; ++j) top[j] = 0;
