@@ -43,13 +43,25 @@ __global__ __launch_bounds__(AM_THREADS) void argmax_chunk_kernel(
     const bool vec = (V % 4 == 0);               // then every row start is 16-byte aligned
     if (vec) {
         const float4* row4 = reinterpret_cast<const float4*>(row);
-        for (int32_t qd = q0 + tid; qd < q1; qd += AM_THREADS) {
-            float4 x = row4[qd];
-            int32_t base = qd * 4;
-            arg_take(bv, bi, x.x, base);
-            arg_take(bv, bi, x.y, base + 1);
-            arg_take(bv, bi, x.z, base + 2);
-            arg_take(bv, bi, x.w, base + 3);
+        constexpr int U = 4;                         // 16-byte loads in flight per thread
+        for (int32_t qd = q0 + tid; qd < q1; qd += U * AM_THREADS) {
+            float4 x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int32_t qu = qd + u * AM_THREADS;
+                x[u] = row4[qu < q1 ? qu : qd];      // a lane past the end re-reads its first quad (skipped below)
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int32_t qu = qd + u * AM_THREADS;
+                if (qu < q1) {
+                    const int32_t base = qu * 4;
+                    arg_take(bv, bi, x[u].x, base);
+                    arg_take(bv, bi, x[u].y, base + 1);
+                    arg_take(bv, bi, x[u].z, base + 2);
+                    arg_take(bv, bi, x[u].w, base + 3);
+                }
+            }
         }
     } else {
         const int32_t e0 = q0 * 4, e1 = (q1 * 4) < V ? (q1 * 4) : V;

@@ -101,3 +101,17 @@ def test_compact_after_a_real_step():
              B=w.B, dtype="bf16")
     ref = _both(c)
     assert ref["status"].tolist() == [0] and ref["new_prefix_len"][0] == w.P + a["accept_len"][0] + 1
+
+
+def test_compact_at_the_32k_prefix_size():
+    """Workload c3's cache (134 MB per side, one layer) after a real acceptance."""
+    w = inputs.get_workload("c3")
+    s = inputs.make_step_inputs(w)
+    att = inputs.make_attention_inputs(w)
+    a = oracle.accept(s["parent"], s["tokens"], s["n_nodes"], 16, target_ids=s["target_ids"])
+    assert a["accept_len"][0] >= 1
+    c = dict(k=att["k_cache"][0].reshape(-1), v=att["v_cache"][0].reshape(-1), table=att["block_table"],
+             strides=att["strides"], layer_stride=0, n_layers=1, P=s["prefix_len"], path=a["path"],
+             acc=a["accept_len"], K=w.K, Hkv=w.Hkv, D=w.D, B=w.B, dtype="bf16")
+    ref = _both(c)
+    assert ref["new_prefix_len"][0] == w.P + a["accept_len"][0] + 1

@@ -98,7 +98,7 @@ def test_update_ties_everywhere():
     assert ref["M"][13].tolist() == [4997, 4998, 4999, 0, 1, 2, 3, 4]
 
 
-@pytest.mark.parametrize("wl", ["c1", "c2"])
+@pytest.mark.parametrize("wl", ["c1", "c2", "c3", "c4"])
 def test_update_at_workload_size_and_accept_takes_its_ids(wl):
     w = inputs.get_workload(wl)
     s = inputs.make_step_inputs(w, with_logits=True)
