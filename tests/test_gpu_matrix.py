@@ -125,3 +125,19 @@ def test_update_then_retrieve_round_trip():
     graft.graft_matrix_retrieve(M, dev(tp), dev(tr), dev([8]), t, p, n)
     torch.cuda.synchronize()
     assert host(t)[0, 1:].tolist() == np.argsort(-logits[0, 0], kind="stable")[:8].tolist()
+
+
+def test_update_from_a_prefill():
+    """App. A Alg. 1 "Update M with prefill logits": a prompt of 4096 positions handed over as 32 rows of 128
+    nodes; tokens repeat heavily (Zipf), the last occurrence of a token decides its row."""
+    rng = np.random.default_rng(12)
+    V, k, L = 4096, 8, 4096
+    ranks = np.minimum(rng.zipf(1.3, L), V) - 1
+    tokens = rng.permutation(V)[ranks].astype(np.int32).reshape(32, 128)
+    logits = rng.standard_normal((32, 128, V)).astype(np.float32)
+    n_nodes = np.full(32, 128, np.int32)
+    n_nodes[-1] = 77                                                      # a ragged last row
+    ref = _update_both(np.full((V, k), -1, np.int32), tokens, n_nodes, logits)
+    touched = {int(t) for b in range(32) for t in tokens[b, :n_nodes[b]]}
+    assert len(touched) < L // 2                                          # the repetition is real
+    assert ((ref["M"][:, 0] >= 0) == np.isin(np.arange(V), list(touched))).all()
