@@ -75,7 +75,7 @@ struct AttnParams {
     const int32_t* prefix_len;
     const int32_t* n_nodes;
     const u64* mask;
-    float* ws_o;        // [B][Hkv][splits][R_pad][D]
+    float* ws_o;        // [B][Hkv][splits][R_pad/16][D/16] tiles of 1 KB: [lane][4], lane = MFMA accumulator lane
     float* ws_ml;       // [B][Hkv][splits][R_pad][2]  (max in log2 units, sum)
     int64_t page_stride, token_stride, head_stride;
     int32_t max_pages, B, K_max, Hq, Hkv, G, R, R_pad, n_splits, n_row_tiles;
@@ -574,8 +574,13 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     const int split = unit % p.n_splits;
     const int g = (unit / p.n_splits) % p.Hkv, b = unit / (p.n_splits * p.Hkv);
 
-    // Q rows of this wavefront: the loads are issued first so that their latency overlaps the
-    // set-up below (rows past R read row 0 and are zeroed when converted)
+    // The set-up is a chain of dependent trips to memory (lengths -> block table -> first
+    // keys), so everything that does not depend on the lengths is requested alongside them:
+    // the lengths first (vector memory returns in order, and they are waited for first), then
+    // this wavefront's Q rows and the sequence's ancestor masks.
+    const int n_raw = p.n_nodes[b];
+    const int P_raw = p.prefix_len[b];
+    // Q rows of this wavefront (rows past R read row 0 and are zeroed when converted)
     const int r_base = rt * (AT_WAVES * 16 * MB) + wave_u * (16 * MB);
     uintx4 qd[MB][4];
 #pragma unroll
@@ -589,11 +594,18 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         for (int ds = 0; ds < 4; ++ds) qd[rb][ds] = *reinterpret_cast<const uintx4*>(qp + 32 * ds);
     }
 
+    // ancestor masks as 32-bit words: two rounds of 256 cover the 64 nodes x 4 x 64 bits
+    static_assert(GRAFT_MAX_NODES * GRAFT_MASK_WORDS * 2 <= 2 * AT_THREADS, "mask words per thread");
+    const int n_mask_words = p.K_max * GRAFT_MASK_WORDS * 2;
+    const unsigned* mask_words = reinterpret_cast<const unsigned*>(p.mask) + static_cast<size_t>(b) * n_mask_words;
+    const unsigned mw0 = tid < n_mask_words ? mask_words[tid] : 0u;
+    const unsigned mw1 = tid + AT_THREADS < n_mask_words ? mask_words[tid + AT_THREADS] : 0u;
+
     SplitRange sr;
-    int n = p.n_nodes[b];
+    int n = n_raw;
     if (n < 1 || n > p.K_max) n = 0;
     const int cap = p.max_pages * GRAFT_PAGE_SIZE;
-    int P = p.prefix_len[b];
+    int P = P_raw;
     P = P < 0 ? 0 : (P > cap ? cap : P);
     sr.n = n;
     sr.P = P;
@@ -605,20 +617,31 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     if (sr.st1 < sr.st0) sr.st1 = sr.st0;
     const int n_st = sr.st1 - sr.st0;
 
+    // this split's block-table entries: the first 1024 are requested before anything is
+    // stored (one trip for all of them), a longer split takes the plain loop for the rest
+    int32_t tbv[4];
+    const int n_pg = n_st * (AT_STAGE / GRAFT_PAGE_SIZE);
+    const int32_t* table = p.block_table + static_cast<size_t>(b) * p.max_pages;
+    const int first_pg = sr.st0 * (AT_STAGE / GRAFT_PAGE_SIZE);
+    const int last_pg = (sr.total - 1) >> 4;
+    {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int pg = first_pg + tid + u * AT_THREADS;
+            tbv[u] = (tid + u * AT_THREADS) < n_pg ? table[pg < last_pg ? pg : last_pg] : 0;
+        }
+    }
     // the first pipeline step multiplies zero probabilities with whatever buffer 3 holds: make it zeros
     for (int k = tid; k < AT_STAGE * AT_ROW_BYTES / 16; k += AT_THREADS)
         reinterpret_cast<uint4*>(&kv[AT_NBUF - 1][AT_STAGE * AT_ROW_BYTES])[k] = uint4{0u, 0u, 0u, 0u};
-    for (int k = tid; k < p.K_max * GRAFT_MASK_WORDS * 2; k += AT_THREADS)
-        Ms[k] = reinterpret_cast<const unsigned*>(p.mask)[static_cast<size_t>(b) * p.K_max * GRAFT_MASK_WORDS * 2 + k];
-    {
-        const int32_t* table = p.block_table + static_cast<size_t>(b) * p.max_pages;
-        const int first_pg = sr.st0 * (AT_STAGE / GRAFT_PAGE_SIZE);
-        const int n_pg = n_st * (AT_STAGE / GRAFT_PAGE_SIZE);
-        const int last_pg = (sr.total - 1) >> 4;
-        for (int k = tid; k < n_pg; k += AT_THREADS) {
-            const int pg = first_pg + k;
-            Tb[k] = table[pg < last_pg ? pg : last_pg];
-        }
+    if (tid < n_mask_words) Ms[tid] = mw0;
+    if (tid + AT_THREADS < n_mask_words) Ms[tid + AT_THREADS] = mw1;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (tid + u * AT_THREADS < n_pg) Tb[tid + u * AT_THREADS] = tbv[u];
+    for (int k = tid + 4 * AT_THREADS; k < n_pg; k += AT_THREADS) {
+        const int pg = first_pg + k;
+        Tb[k] = table[pg < last_pg ? pg : last_pg];
     }
     __syncthreads();
 
@@ -808,12 +831,14 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     }
     GRAFT_MFMA_SETTLE();
 
-    // ---- partial results: unnormalised O, reference max (log2 units), row sum
+    // ---- partial results: unnormalised O, reference max (log2 units), row sum.  O is written
+    //      as the accumulator tiles lie in the registers (16 rows x 16 dims, 16 bytes per lane):
+    //      every store instruction then fills 1 KB of consecutive addresses.
     const size_t part = ((static_cast<size_t>(b) * p.Hkv + g) * p.n_splits + split) * p.R_pad;
     static_for<0, MB>([&](auto rb_) {
         GRAFT_CONST(rb, rb_);
-        const int r = r_base + rb * 16 + l16;
-        float* op = p.ws_o + (part + r) * AT_D + 4 * lg;
+        const int r0 = r_base + rb * 16;                          // first row of this 16-row block
+        float* op = p.ws_o + (part + r0) * AT_D + 4 * lane;
         static_for<0, 8>([&](auto db_) {
             GRAFT_CONST(db, db_);
             floatx4 t;
@@ -821,80 +846,89 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             t[1] = acc_get<o_reg(rb, db) + 1>();
             t[2] = acc_get<o_reg(rb, db) + 2>();
             t[3] = acc_get<o_reg(rb, db) + 3>();
-            *reinterpret_cast<floatx4*>(op + 16 * db) = t;
+            *reinterpret_cast<floatx4*>(op + 256 * db) = t;
         });
         if (lg == 0) {
-            float* ml = p.ws_ml + (part + r) * 2;
+            float* ml = p.ws_ml + (part + r0 + l16) * 2;
             ml[0] = w.m_ref[rb];
             ml[1] = w.lsum[rb][0];
         }
     });
 }
 
-// Weighted sum of one row's partial results, U splits per step with all U loads in flight.
+// Merge the splits of one 16-row x 16-dim output tile: out = sum_s w_s O_s / sum_s w_s l_s with
+// w_s = 2^(m_s - max m).  One wavefront per tile; lane (l16, lg) owns row l16, dims 4 lg .. +3,
+// exactly the 16 bytes it holds of every split's partial tile, so a split is one 1 KB read.
+// U splits are read per step with all their loads in flight (no branch in between: a split
+// without keys has weight 0 and a zero partial tile); the maximum is a running one, and what
+// has been summed is rescaled when a later step raises it.
 template <int U>
-__device__ __forceinline__ void combine_rows(const float* orow, size_t split_stride, int ns, float w_s,
-                                             float& acc0, float& acc1) {
+__device__ __forceinline__ void combine_tiles(const float* otile, const float* mlrow, size_t o_stride,
+                                              size_t ml_stride, int ns, floatx4& acc, float& den) {
+    float m_run = -INFINITY;
     for (int s0 = 0; s0 < ns; s0 += U) {
-        float2 ov[U];
+        floatx4 ov[U];
+        float2 ml[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int sc = (s0 + u) < ns ? (s0 + u) : (ns - 1);
-            ov[u] = *reinterpret_cast<const float2*>(orow + sc * split_stride);
+            ov[u] = *reinterpret_cast<const floatx4*>(otile + sc * o_stride);
+            ml[u] = *reinterpret_cast<const float2*>(mlrow + sc * ml_stride);
         }
+        float m_new = m_run;
+#pragma unroll
+        for (int u = 0; u < U; ++u) m_new = fmaxf(m_new, ml[u].x);       // a repeated last split changes nothing
+        const float keep = m_run > -INFINITY ? __builtin_amdgcn_exp2f(m_run - m_new) : 0.f;
+        den *= keep;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] *= keep;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float wu = (s0 + u) < ns ? __shfl(w_s, s0 + u) : 0.f;
-            acc0 += wu * ov[u].x;
-            acc1 += wu * ov[u].y;
+            const bool on = (s0 + u) < ns && ml[u].x > -INFINITY;
+            const float wu = on ? __builtin_amdgcn_exp2f(ml[u].x - m_new) : 0.f;
+            den += wu * ml[u].y;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += wu * ov[u][e];
         }
+        m_run = m_new;
     }
 }
 
-// Merge the splits of one output row: out = sum_s w_s O_s / sum_s w_s l_s, w_s = 2^(m_s - max m).
-// One wavefront per row.  Lane s holds split s's (m, l) and weight; the partial rows are then
-// read up to eight splits at a time with all their loads in flight (no branch in between: a
-// split without keys has weight 0 and a zero partial row).
 __global__ __launch_bounds__(AT_THREADS) void tree_attn_combine_kernel(AttnParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t row = static_cast<int64_t>(blockIdx.x) * AT_WAVES + wave;   // over B*K_max*Hq
-    const int64_t n_rows = static_cast<int64_t>(p.B) * p.K_max * p.Hq;
-    if (row >= n_rows) return;
-    const int h = static_cast<int>(row % p.Hq);
-    const int i = static_cast<int>((row / p.Hq) % p.K_max);
-    const int b = static_cast<int>(row / (static_cast<int64_t>(p.Hq) * p.K_max));
-    unsigned short* outp = static_cast<unsigned short*>(p.out) + row * AT_D + 2 * lane;
-    int n = p.n_nodes[b];
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int n_blk = p.R_pad >> 4;                                           // 16-row blocks per (b, g)
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * AT_WAVES + wave;  // over B*Hkv*n_blk*8
+    const int64_t n_tiles = static_cast<int64_t>(p.B) * p.Hkv * n_blk * (AT_D / 16);
+    if (tile >= n_tiles) return;
+    const int db = static_cast<int>(tile & 7);
+    const int blk = static_cast<int>((tile >> 3) % n_blk);
+    const int64_t bg = (tile >> 3) / n_blk;                                   // b * Hkv + g
+    const int g = static_cast<int>(bg % p.Hkv), b = static_cast<int>(bg / p.Hkv);
+    const int r = blk * 16 + l16;
+    if (r >= p.R) return;                                                      // padding rows of the tile
+    int n = p.n_nodes[b];                                                      // needed only at the end
+    const int i = (r * p.g_magic) >> 16, hl = r - i * p.G;                     // i = r / G
+    unsigned short* outp = static_cast<unsigned short*>(p.out) +
+        ((static_cast<int64_t>(b) * p.K_max + i) * p.Hq + g * p.G + hl) * AT_D + 16 * db + 4 * lg;
+    const int ns = p.n_splits;
+    const size_t base = static_cast<size_t>(bg) * ns * p.R_pad + blk * 16;     // row index of split 0
+    const float* mlrow = p.ws_ml + (base + l16) * 2;
+    const size_t ml_stride = static_cast<size_t>(p.R_pad) * 2;
+    const float* otile = p.ws_o + base * AT_D + 256 * db + 4 * lane;
+    const size_t o_stride = static_cast<size_t>(p.R_pad) * AT_D;
+    floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
+    if (ns >= 16) combine_tiles<16>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
+    else if (ns >= 8) combine_tiles<8>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
+    else if (ns >= 4) combine_tiles<4>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
+    else combine_tiles<2>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
     if (n < 1 || n > p.K_max) n = 0;
-    if (i >= n) {
-        *reinterpret_cast<unsigned*>(outp) = 0u;
-        return;
-    }
-    const int g = h / p.G, r = i * p.G + (h - g * p.G);
-    const size_t base = (static_cast<size_t>(b) * p.Hkv + g) * p.n_splits * p.R_pad + r;
-    const int ns = p.n_splits;                                   // <= AT_MAX_SPLITS = 64
-    float m_s = -INFINITY, l_s = 0.f;
-    if (lane < ns) {
-        const float2 ml = *reinterpret_cast<const float2*>(p.ws_ml + (base + static_cast<size_t>(lane) * p.R_pad) * 2);
-        m_s = ml.x;
-        l_s = ml.y;
-    }
-    float mmax = m_s;
-#pragma unroll
-    for (int sft = 32; sft >= 1; sft >>= 1) mmax = fmaxf(mmax, __shfl_xor(mmax, sft));
-    const float w_s = m_s == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_s - mmax);
-    float den = w_s * l_s;
-#pragma unroll
-    for (int sft = 32; sft >= 1; sft >>= 1) den += __shfl_xor(den, sft);
-    float acc0 = 0.f, acc1 = 0.f;
-    const float* orow = p.ws_o + base * AT_D + 2 * lane;
-    const size_t split_stride = static_cast<size_t>(p.R_pad) * AT_D;
-    if (ns >= 8) combine_rows<8>(orow, split_stride, ns, w_s, acc0, acc1);
-    else if (ns >= 4) combine_rows<4>(orow, split_stride, ns, w_s, acc0, acc1);
-    else combine_rows<2>(orow, split_stride, ns, w_s, acc0, acc1);
     const float inv = den > 0.f ? 1.0f / den : 0.f;
-    const unsigned lo = float_to_bf16_bits(acc0 * inv), hi = float_to_bf16_bits(acc1 * inv);
-    *reinterpret_cast<unsigned*>(outp) = lo | (hi << 16);
+    unsigned o01 = float_to_bf16_bits(acc[0] * inv) | (float_to_bf16_bits(acc[1] * inv) << 16);
+    unsigned o23 = float_to_bf16_bits(acc[2] * inv) | (float_to_bf16_bits(acc[3] * inv) << 16);
+    if (i >= n) o01 = o23 = 0u;              // rows of absent nodes are zeros whatever their Q rows held
+    *reinterpret_cast<uint2*>(outp) = uint2{o01, o23};
 }
 
 // ---------------------------------------------------------------------------
@@ -1177,8 +1211,8 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     }
     int32_t rc = check_launch();
     if (rc != GRAFT_OK) return rc;
-    const int64_t n_rows = static_cast<int64_t>(B) * K_max * Hq;
-    hipLaunchKernelGGL(tree_attn_combine_kernel, dim3(static_cast<unsigned>((n_rows + AT_WAVES - 1) / AT_WAVES)),
+    const int64_t n_tiles = static_cast<int64_t>(B) * Hkv * (pl.r_pad / 16) * (AT_D / 16);
+    hipLaunchKernelGGL(tree_attn_combine_kernel, dim3(static_cast<unsigned>((n_tiles + AT_WAVES - 1) / AT_WAVES)),
                        dim3(AT_THREADS), 0, s, p);
     return check_launch();
 }
