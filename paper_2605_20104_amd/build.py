@@ -61,8 +61,9 @@ def check_attention_asm(asm_text: str):
     their hand-placed registers and inline-assembly MFMAs rely on.  Returns a list of
     violations (empty = fine):
       * no scratch memory (register spills) in any of the kernels;
-      * outside the inline-assembly blocks no instruction names an AccVGPR below 48 * MB (the
-        accumulators and the Q operand live there and the compiler must not touch them);
+      * outside the inline-assembly blocks no instruction names an AccVGPR below
+        48 * MB + 4 * min(MB, 4) (the accumulators, the Q operand and the row sums live there
+        and the compiler must not touch them);
       * no MFMA has a vector ALU instruction writing one of its VGPR sources within the two
         preceding wait states (an s_nop k counts k + 1): the hardware needs them and the
         compiler does not know that the asm statement is an MFMA.
@@ -109,7 +110,7 @@ def check_attention_asm(asm_text: str):
         if not in_asm:
             for a in args:
                 sp = _reg_span(a)
-                if sp and sp[0] == "a" and sp[1] < 48 * mb:
+                if sp and sp[0] == "a" and sp[1] < 48 * mb + 4 * min(mb, 4):
                     problems.append("line %d (%s): compiler-generated use of a hand-managed AccVGPR: %s"
                                     % (ln, kernel, text))
         if op.startswith("v_mfma"):

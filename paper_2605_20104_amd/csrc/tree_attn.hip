@@ -152,6 +152,8 @@ __device__ __forceinline__ void lds_barrier() {
 //   O^T accumulators of row block rb, dim block db : a[32 rb + 4 db .. +3], accumulated in
 //       place and never touched by the vector ALUs inside the fast loop;
 //   Q^T operand of row block rb < QA, dim step ds   : a[32 MB + 16 rb + 4 ds .. +3];
+//   row sums of row block rb < 4                     : a[48 MB + 4 rb .. +3] (a fifth row block's
+//       are in VGPRs: 48 * 5 + 16 = 256 is the whole AccVGPR file);
 //   score tiles, probabilities, K/V operands        : VGPRs chosen by the compiler.
 // The compiler itself uses no AccVGPR in this kernel (VGPR-to-AccVGPR spilling is switched
 // off in the build, and the kernel must compile without spills); the asm statement in
@@ -182,9 +184,11 @@ __device__ __forceinline__ void static_for(F&& f) {
 #define GRAFT_CONST(name, ic) constexpr int name = decltype(ic)::value
 
 template <int MB> constexpr int q_in_acc() { return MB; }   // row blocks with Q^T in AccVGPRs (all, for MB <= 5)
-template <int MB> constexpr int acc_used() { return 32 * MB + 16 * q_in_acc<MB>(); }
+constexpr int L_IN_ACC = 4;                                  // row blocks with their row sums in AccVGPRs
+template <int MB> constexpr int acc_used() { return 32 * MB + 16 * q_in_acc<MB>() + 4 * (MB < L_IN_ACC ? MB : L_IN_ACC); }
 constexpr int o_reg(int rb, int db) { return 32 * rb + 4 * db; }
 template <int MB> constexpr int q_reg(int rb, int ds) { return 32 * MB + 16 * rb + 4 * ds; }
+template <int MB> constexpr int l_reg(int rb) { return 48 * MB + 4 * rb; }
 
 template <int MB>
 __device__ __forceinline__ void reserve_acc_registers() {
@@ -252,7 +256,15 @@ __device__ __forceinline__ void mfma_o(const bf16x8& va, const uintx4& pb) {
         asm volatile("v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]"
                      : : "n"(OR), "n"(OR + 3), "v"(va), "v"(pb));
 }
-// row sums (VGPRs) += ones x P^T operand: every element of the tile ends up holding the row's sum
+// row sums += ones x P^T operand: every element of the tile ends up holding the row's sum.
+// In AccVGPRs a[LR .. LR+3], or (a fifth row block) in VGPRs.
+template <int LR, bool GUARD = false>
+__device__ __forceinline__ void mfma_rowsum_acc(const bf16x8& ones, const uintx4& pb) {
+    if constexpr (GUARD)
+        asm volatile(GRAFT_MFMA_GUARD "v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]" : : "n"(LR), "n"(LR + 3), "v"(ones), "v"(pb));
+    else
+        asm volatile("v_mfma_f32_16x16x32_bf16 a[%0:%1], %2, %3, a[%0:%1]" : : "n"(LR), "n"(LR + 3), "v"(ones), "v"(pb));
+}
 template <bool GUARD = false>
 __device__ __forceinline__ void mfma_rowsum(floatx4& l, const bf16x8& ones, const uintx4& pb) {
     if constexpr (GUARD)
@@ -285,10 +297,13 @@ __device__ __forceinline__ unsigned opaque_bits(unsigned v) {
 // result q'.k - m_ref is directly the argument of exp2.
 template <int MB>
 struct WaveRows {
-    floatx4 negm[MB];       // {-m_ref} x 4: accumulator input of the first QK^T step (0 while unset)
-    floatx4 lsum[MB];       // row sums of the bf16 probabilities (all four elements equal)
-    float m_ref[MB];        // reference max of the row in log2 units (-inf: not set yet)
-    float thr[MB];          // an exponent above this needs attention: -inf while unset, else the lazy bound
+    floatx4 negm[MB];       // {-m_ref} x 4: accumulator input of the first QK^T step (0 while unset);
+                            // m_ref is the reference max of the row in log2 units
+    floatx4 lsum_v;         // row sums of a fifth row block (the others' are in AccVGPRs)
+    float thr[MB];          // an exponent above this needs attention: -inf while the row has no reference
+                            // yet, else the lazy bound
+    __device__ __forceinline__ bool unset(int rb) const { return thr[rb] == -INFINITY; }
+    __device__ __forceinline__ float m_ref(int rb) const { return unset(rb) ? -INFINITY : -negm[rb][0]; }
 };
 
 // LDS byte offsets of this lane's MFMA operands inside a 32-token sub-tile.
@@ -317,17 +332,26 @@ __device__ __forceinline__ bf16x8 load_v_operand(const unsigned char* Vs, int db
     return va;
 }
 
+// The vector ALUs are the scarce resource of the pipeline: next to one MFMA the wavefront
+// can issue one exponential, or two plain vector instructions, without delaying the next
+// MFMA.  Region 1 therefore exponentiates only the first rows_early<MB>() row blocks; the
+// last ("late") row block's probabilities are computed one region earlier, in region 2,
+// whose other vector work (the maximum scan) leaves slots free.
+template <int MB> constexpr int rows_early() { return MB >= 2 ? MB - 1 : MB; }
+
 // Pipeline region 1: the matrix cores compute the exponents of the NEXT sub-tile
 // (X^T = K Q'^T - m_ref into xn) while the vector ALUs turn the CURRENT sub-tile's exponents
-// xc into probabilities (pb, packed bf16).  One MFMA and one exponential per slot;
-// sched_barrier pins the interleaving because the wavefront issues in order.
+// xc into probabilities (pb, packed bf16) for the early row blocks.  One MFMA and one
+// exponential per slot; sched_barrier pins the interleaving because the wavefront issues in
+// order.
 template <int MB>
 __device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ Ks, const WaveRows<MB>& w,
                                               floatx4 (&xn)[MB][2], const floatx4 (&xc)[MB][2],
                                               uintx4 (&pb)[MB], int lane) {
+    constexpr int E = rows_early<MB>();
     const int l16 = lane & 15, lg = lane >> 4;
     bf16x8 ka[3];
-    float e0[MB], e1[MB];       // exponentials waiting to be packed (a pair is packed one group later)
+    float e0[E], e1[E];         // exponentials waiting to be packed (a pair is packed one group later)
     ka[0] = load_k_operand(Ks, 0, l16, lg);
     ka[1] = load_k_operand(Ks, 1, l16, lg);
     static_for<0, 8>([&](auto g_) {
@@ -339,28 +363,51 @@ __device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ 
             constexpr bool guard = (g == 0 && rb == 0);
             if constexpr (ds == 0) mfma_x_first<q_reg<MB>(rb, 0), guard>(xn[rb][c], ka[g % 3], w.negm[rb]);
             else mfma_x_next<q_reg<MB>(rb, ds), guard>(xn[rb][c], ka[g % 3]);
-            if constexpr ((g & 1) == 0 && g >= 2) pb[rb][(g - 2) >> 1] = pack_bf16(e0[rb], e1[rb]);
-            const float pe = __builtin_amdgcn_exp2f(xc[rb][c][ds]);
-            if constexpr (g & 1) e1[rb] = pe;
-            else e0[rb] = pe;
+            if constexpr (rb < E) {
+                if constexpr ((g & 1) == 0 && g >= 2) pb[rb][(g - 2) >> 1] = pack_bf16(e0[rb], e1[rb]);
+                const float pe = __builtin_amdgcn_exp2f(xc[rb][c][ds]);
+                if constexpr (g & 1) e1[rb] = pe;
+                else e0[rb] = pe;
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
     });
 #pragma unroll
-    for (int rb = 0; rb < MB; ++rb) pb[rb][3] = pack_bf16(e0[rb], e1[rb]);
+    for (int rb = 0; rb < E; ++rb) pb[rb][3] = pack_bf16(e0[rb], e1[rb]);
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// Probabilities of the late row block from its exponents, outside the pipeline: after the
+// exponents were changed behind region 2's back (ancestor masking, a new reference).
+template <int MB>
+__device__ __forceinline__ void late_probabilities(const floatx4 (&x)[MB][2], uintx4& pl) {
+    if constexpr (rows_early<MB>() < MB) {
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(x[MB - 1][e >> 2][e & 3]);
+            const float p1 = __builtin_amdgcn_exp2f(x[MB - 1][e >> 2][(e & 3) + 1]);
+            pl[e >> 1] = pack_bf16(p0, p1);
+        }
+    }
+}
+
 // Pipeline region 2: the matrix cores run O^T += V^T P^T and the row sums of the CURRENT
-// sub-tile while the vector ALUs scan the NEXT sub-tile's exponents for their lane-local
-// maxima.  Returns whether any lane saw an exponent above its row's threshold
-// (wavefront-uniform).
+// sub-tile (probabilities: pb for the early row blocks, pl_cur for the late one) while the
+// vector ALUs scan the NEXT sub-tile's exponents xn for their lane-local maxima (first half
+// of the region) and turn the late row block's into probabilities pl_next (second half;
+// speculative: the caller redoes them when the scan or the masking changes the exponents).
+// Returns whether any lane saw an exponent above its row's threshold (wavefront-uniform).
 template <int MB>
 __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ Vs, WaveRows<MB>& w,
-                                              const uintx4 (&pb)[MB], const floatx4 (&xn)[MB][2],
-                                              const bf16x8& ones, float (&lm)[MB], int lane) {
+                                              const uintx4 (&pb)[MB], const uintx4& pl_cur, uintx4& pl_next,
+                                              const floatx4 (&xn)[MB][2], const bf16x8& ones, float ninf,
+                                              float (&lm)[MB], int lane) {
+    constexpr int E = rows_early<MB>();
+    constexpr bool LATE = E < MB;
+    constexpr bool INLOOP = LATE && MB >= 3;     // three free slots per group are needed
     const int l16 = lane & 15, lg = lane >> 4;
     bf16x8 va[3];
+    float le0 = 0.f, le1 = 0.f;
     va[0] = load_v_operand(Vs, 0, l16, lg);
     va[1] = load_v_operand(Vs, 1, l16, lg);
     static_for<0, 8>([&](auto db_) {
@@ -368,24 +415,40 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
         if constexpr (db + 2 < 8) va[(db + 2) % 3] = load_v_operand(Vs, db + 2, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
-            mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(va[db % 3], pb[rb]);
+            if constexpr (rb < E) mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(va[db % 3], pb[rb]);
+            else mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(va[db % 3], pl_cur);
             if constexpr (db < 4) {          // two exponents per slot: 4 slots cover the row block's 8
                 const float a = xn[rb][db >> 1][2 * (db & 1)], b = xn[rb][db >> 1][2 * (db & 1) + 1];
-                lm[rb] = db == 0 ? __builtin_fmaxf(a, b) : __builtin_fmaxf(__builtin_fmaxf(lm[rb], a), b);
+                // (the three-operand form also for the first pair: a plain two-operand
+                // maximum would first canonicalise both inputs, two more instructions)
+                lm[rb] = __builtin_fmaxf(__builtin_fmaxf(db == 0 ? ninf : lm[rb], a), b);
+            } else if constexpr (INLOOP && rb <= 1) {
+                // late row block: element 2 (db - 4) + rb of its 8; a pair is packed in the slot
+                // after its second exponential
+                constexpr int e = 2 * (db - 4) + rb;
+                const float pe = __builtin_amdgcn_exp2f(xn[MB - 1][e >> 2][e & 3]);
+                if constexpr (rb == 0) le0 = pe;
+                else le1 = pe;
+            } else if constexpr (INLOOP && rb == 2) {
+                pl_next[db - 4] = pack_bf16(le0, le1);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
     });
+    if constexpr (LATE && !INLOOP) late_probabilities<MB>(xn, pl_next);
     static_for<0, MB>([&](auto rb_) {
         GRAFT_CONST(rb, rb_);
-        mfma_rowsum(w.lsum[rb], ones, pb[rb]);
+        if constexpr (rb >= L_IN_ACC) mfma_rowsum(w.lsum_v, ones, rb < E ? pb[rb] : pl_cur);
+        else if constexpr (rb < E) mfma_rowsum_acc<l_reg<MB>(rb)>(ones, pb[rb]);
+        else mfma_rowsum_acc<l_reg<MB>(rb)>(ones, pl_cur);
     });
     bool grow = false;
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) grow = grow || (lm[rb] > w.thr[rb]);
     const bool any = __builtin_amdgcn_ballot_w64(grow) != 0;
 #pragma unroll
-    for (int rb = 0; rb < MB; ++rb) GRAFT_KEEP(pb[rb]);
+    for (int rb = 0; rb < E; ++rb) GRAFT_KEEP(pb[rb]);
+    GRAFT_KEEP(pl_cur);
     return any;
 }
 
@@ -441,14 +504,12 @@ __device__ __forceinline__ bool set_references(float (&lm)[MB], WaveRows<MB>& w,
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         lm[rb] = mx;                                      // now the row maximum, same in the row's 4 lanes
-        const bool unset = w.m_ref[rb] == -INFINITY;
-        raise = raise || (!unset && mx > w.thr[rb]);
+        raise = raise || (!w.unset(rb) && mx > w.thr[rb]);
     }
     if (__builtin_amdgcn_ballot_w64(raise) != 0) return true;
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) {
-        if (w.m_ref[rb] == -INFINITY && lm[rb] > -INFINITY) {
-            w.m_ref[rb] = lm[rb];
+        if (w.unset(rb) && lm[rb] > -INFINITY) {
             w.negm[rb] = floatx4{-lm[rb], -lm[rb], -lm[rb], -lm[rb]};
             w.thr[rb] = AT_LAZY_LOG2;
 #pragma unroll
@@ -468,18 +529,23 @@ __device__ __forceinline__ void raise_references(const float (&lm)[MB], WaveRows
     static_for<0, MB>([&](auto rb_) {
         GRAFT_CONST(rb, rb_);
         const float mx = lm[rb];
-        const bool unset = w.m_ref[rb] == -INFINITY;
+        const bool unset = w.unset(rb);
         const bool move = (!unset && mx > 0.0f) || (unset && mx > -INFINITY);
         if (__builtin_amdgcn_ballot_w64(move) != 0) {
             // rows that do not move get a = 1 and a zero shift
             const float shift = move ? mx : 0.0f;
             const float a = move ? (unset ? 0.0f : __builtin_amdgcn_exp2f(-mx)) : 1.0f;
             if (move) {
-                w.m_ref[rb] = (unset ? 0.0f : w.m_ref[rb]) + mx;
-                w.negm[rb] = floatx4{-w.m_ref[rb], -w.m_ref[rb], -w.m_ref[rb], -w.m_ref[rb]};
+                const float nm = (unset ? 0.0f : w.negm[rb][0]) - mx;
+                w.negm[rb] = floatx4{nm, nm, nm, nm};
                 w.thr[rb] = AT_LAZY_LOG2;
             }
-            w.lsum[rb] *= a;
+            if constexpr (rb >= L_IN_ACC) w.lsum_v *= a;
+            else
+                static_for<0, 4>([&](auto k_) {
+                    GRAFT_CONST(k, k_);
+                    acc_scale<l_reg<MB>(rb) + k>(a);
+                });
             static_for<0, 32>([&](auto k_) {
                 GRAFT_CONST(k, k_);
                 acc_scale<32 * rb + k>(a);
@@ -540,7 +606,8 @@ __device__ __forceinline__ void pv_only(const unsigned char* __restrict__ Vs, Wa
     });
     static_for<0, MB>([&](auto rb_) {
         GRAFT_CONST(rb, rb_);
-        mfma_rowsum<true>(w.lsum[rb], ones, pb[rb]);
+        if constexpr (rb >= L_IN_ACC) mfma_rowsum<true>(w.lsum_v, ones, pb[rb]);
+        else mfma_rowsum_acc<l_reg<MB>(rb), true>(ones, pb[rb]);
         asm volatile("s_nop 7" ::: "memory");
     });
     GRAFT_MFMA_SETTLE();
@@ -721,10 +788,14 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             GRAFT_CONST(k, k_);
             acc_set_bits<q_reg<MB>(rb, 0) + k>(scale_bf16_pair(qd[rb][k >> 2][k & 3], c_row));
         });
-        w.m_ref[rb] = -INFINITY;
         w.thr[rb] = -INFINITY;
         w.negm[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
-        w.lsum[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (rb >= L_IN_ACC) w.lsum_v = floatx4{0.f, 0.f, 0.f, 0.f};
+        else
+            static_for<0, 4>([&](auto k_) {
+                GRAFT_CONST(k, k_);
+                acc_set<l_reg<MB>(rb) + k>(0.0f);
+            });
         static_for<0, 32>([&](auto k_) {
             GRAFT_CONST(k, k_);
             acc_set<32 * rb + k>(0.0f);
@@ -752,7 +823,9 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     //      below (exact running max, rescaling O with the vector ALUs).
     floatx4 xa[MB][2], xb[MB][2];
     uintx4 pb[MB];
+    uintx4 pla = uintx4{0u, 0u, 0u, 0u}, plb = pla;   // late row block's probabilities: even / odd sub-tiles
     float lm[MB];
+    const float ninf = __uint_as_float(opaque_bits(0xff800000u));
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
@@ -774,24 +847,39 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         const unsigned char* prev = kv[(k - 1) & (AT_NBUF - 1)];
         const int t0 = (sr.st0 + k) * AT_STAGE;
         // even sub-tile of stage k
+        // (the late row block's probabilities of the odd sub-tile before, plb, are consumed
+        //  while those of this even sub-tile, pla, are produced; and the other way round below)
         region_qk_exp<MB>(cur + K_OFF, w, xa, xb, pb, lane);
-        bool grow = region_pv_max<MB>(prev + V_OFF + SUB, w, pb, xa, ones, lm, lane);
+        bool grow = region_pv_max<MB>(prev + V_OFF + SUB, w, pb, plb, pla, xa, ones, ninf, lm, lane);
         if (!live) break;
-        if (t0 + AT_SUB > sr.P) grow = apply_tree_mask<MB>(xa, w, lm, lane, t0, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
-        if (grow && set_references<MB>(lm, w, xa)) { slow = true; j = 2 * k; break; }
+        // (where the exponents change after region 2 has turned the late row block's into
+        //  probabilities, those are redone)
+        if (t0 + AT_SUB > sr.P) {
+            grow = apply_tree_mask<MB>(xa, w, lm, lane, t0, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
+            late_probabilities<MB>(xa, pla);
+        }
+        if (grow) {
+            if (set_references<MB>(lm, w, xa)) { slow = true; j = 2 * k; break; }
+            late_probabilities<MB>(xa, pla);
+        }
         // odd sub-tile of stage k
         region_qk_exp<MB>(cur + K_OFF + SUB, w, xb, xa, pb, lane);
-        grow = region_pv_max<MB>(cur + V_OFF, w, pb, xb, ones, lm, lane);
-        if (t0 + 2 * AT_SUB > sr.P)
+        grow = region_pv_max<MB>(cur + V_OFF, w, pb, pla, plb, xb, ones, ninf, lm, lane);
+        if (t0 + 2 * AT_SUB > sr.P) {
             grow = apply_tree_mask<MB>(xb, w, lm, lane, t0 + AT_SUB, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
-        if (grow && set_references<MB>(lm, w, xb)) {
-            slow = true;
-            j = 2 * k + 1;
+            late_probabilities<MB>(xb, plb);
+        }
+        if (grow) {
+            if (set_references<MB>(lm, w, xb)) {
+                slow = true;
+                j = 2 * k + 1;
 #pragma unroll
-            for (int rb = 0; rb < MB; ++rb)
+                for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
-                for (int c = 0; c < 2; ++c) xa[rb][c] = xb[rb][c];
-            break;
+                    for (int c = 0; c < 2; ++c) xa[rb][c] = xb[rb][c];
+                break;
+            }
+            late_probabilities<MB>(xb, plb);
         }
     }
 
@@ -850,8 +938,9 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         });
         if (lg == 0) {
             float* ml = p.ws_ml + (part + r0 + l16) * 2;
-            ml[0] = w.m_ref[rb];
-            ml[1] = w.lsum[rb][0];
+            ml[0] = w.m_ref(rb);
+            if constexpr (rb >= L_IN_ACC) ml[1] = w.lsum_v[0];
+            else ml[1] = acc_get<l_reg<MB>(rb)>();
         }
     });
 }
