@@ -344,25 +344,28 @@ template <int MB> constexpr int rows_early() { return MB >= 2 ? MB - 1 : MB; }
 // xc into probabilities (pb, packed bf16) for the early row blocks.  One MFMA and one
 // exponential per slot; sched_barrier pins the interleaving because the wavefront issues in
 // order.
-template <int MB>
-__device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ Ks, const WaveRows<MB>& w,
+template <int MB, bool FIRST>
+__device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ Ks,
+                                              const unsigned char* __restrict__ Vnext, const WaveRows<MB>& w,
                                               floatx4 (&xn)[MB][2], const floatx4 (&xc)[MB][2],
-                                              uintx4 (&pb)[MB], int lane) {
+                                              uintx4 (&pb)[MB], bf16x8 (&ring)[4], int lane) {
     constexpr int E = rows_early<MB>();
     const int l16 = lane & 15, lg = lane >> 4;
-    bf16x8 ka[3];
     float e0[E], e1[E];         // exponentials waiting to be packed (a pair is packed one group later)
-    ka[0] = load_k_operand(Ks, 0, l16, lg);
-    ka[1] = load_k_operand(Ks, 1, l16, lg);
+    if constexpr (FIRST) {
+        ring[0] = load_k_operand(Ks, 0, l16, lg);
+        ring[1] = load_k_operand(Ks, 1, l16, lg);
+    }
     static_for<0, 8>([&](auto g_) {
         GRAFT_CONST(g, g_);
         constexpr int c = g >> 2, ds = g & 3;
-        if constexpr (g + 2 < 8) ka[(g + 2) % 3] = load_k_operand(Ks, g + 2, l16, lg);
+        if constexpr (g + 2 < 8) ring[(g + 2) & 3] = load_k_operand(Ks, g + 2, l16, lg);
+        else ring[(g + 2) & 3] = load_v_operand(Vnext, g + 2 - 8, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
             constexpr bool guard = (g == 0 && rb == 0);
-            if constexpr (ds == 0) mfma_x_first<q_reg<MB>(rb, 0), guard>(xn[rb][c], ka[g % 3], w.negm[rb]);
-            else mfma_x_next<q_reg<MB>(rb, ds), guard>(xn[rb][c], ka[g % 3]);
+            if constexpr (ds == 0) mfma_x_first<q_reg<MB>(rb, 0), guard>(xn[rb][c], ring[g & 3], w.negm[rb]);
+            else mfma_x_next<q_reg<MB>(rb, ds), guard>(xn[rb][c], ring[g & 3]);
             if constexpr (rb < E) {
                 if constexpr ((g & 1) == 0 && g >= 2) pb[rb][(g - 2) >> 1] = pack_bf16(e0[rb], e1[rb]);
                 const float pe = __builtin_amdgcn_exp2f(xc[rb][c][ds]);
@@ -397,26 +400,25 @@ __device__ __forceinline__ void late_probabilities(const floatx4 (&x)[MB][2], ui
 // of the region) and turn the late row block's into probabilities pl_next (second half;
 // speculative: the caller redoes them when the scan or the masking changes the exponents).
 // Returns whether any lane saw an exponent above its row's threshold (wavefront-uniform).
-template <int MB>
-__device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ Vs, WaveRows<MB>& w,
+template <int MB, bool LAST>
+__device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ Vs,
+                                              const unsigned char* __restrict__ Knext, WaveRows<MB>& w,
                                               const uintx4 (&pb)[MB], const uintx4& pl_cur, uintx4& pl_next,
                                               const floatx4 (&xn)[MB][2], const bf16x8& ones, float ninf,
-                                              float (&lm)[MB], int lane) {
+                                              float (&lm)[MB], bf16x8 (&ring)[4], int lane) {
     constexpr int E = rows_early<MB>();
     constexpr bool LATE = E < MB;
     constexpr bool INLOOP = LATE && MB >= 3;     // three free slots per group are needed
     const int l16 = lane & 15, lg = lane >> 4;
-    bf16x8 va[3];
     float le0 = 0.f, le1 = 0.f;
-    va[0] = load_v_operand(Vs, 0, l16, lg);
-    va[1] = load_v_operand(Vs, 1, l16, lg);
     static_for<0, 8>([&](auto db_) {
         GRAFT_CONST(db, db_);
-        if constexpr (db + 2 < 8) va[(db + 2) % 3] = load_v_operand(Vs, db + 2, l16, lg);
+        if constexpr (db + 2 < 8) ring[(db + 2) & 3] = load_v_operand(Vs, db + 2, l16, lg);
+        else if constexpr (!LAST) ring[(db + 2) & 3] = load_k_operand(Knext, db + 2 - 8, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
-            if constexpr (rb < E) mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(va[db % 3], pb[rb]);
-            else mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(va[db % 3], pl_cur);
+            if constexpr (rb < E) mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(ring[db & 3], pb[rb]);
+            else mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(ring[db & 3], pl_cur);
             if constexpr (db < 4) {          // two exponents per slot: 4 slots cover the row block's 8
                 const float a = xn[rb][db >> 1][2 * (db & 1)], b = xn[rb][db >> 1][2 * (db & 1) + 1];
                 // (the three-operand form also for the first pair: a plain two-operand
@@ -431,6 +433,9 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
                 else le1 = pe;
             } else if constexpr (INLOOP && rb == 2) {
                 pl_next[db - 4] = pack_bf16(le0, le1);
+                // (pinned here: the caller overwrites pl_next on some paths, and the compiler
+                //  would otherwise move these exponentials to the paths that do not)
+                asm volatile("" : "+v"(pl_next[db - 4]));
             }
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -826,6 +831,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     uintx4 pla = uintx4{0u, 0u, 0u, 0u}, plb = pla;   // late row block's probabilities: even / odd sub-tiles
     float lm[MB];
     const float ninf = __uint_as_float(opaque_bits(0xff800000u));
+    bf16x8 ring[4];            // MFMA operands read ahead from LDS (see the regions)
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb)
 #pragma unroll
@@ -849,8 +855,8 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         // even sub-tile of stage k
         // (the late row block's probabilities of the odd sub-tile before, plb, are consumed
         //  while those of this even sub-tile, pla, are produced; and the other way round below)
-        region_qk_exp<MB>(cur + K_OFF, w, xa, xb, pb, lane);
-        bool grow = region_pv_max<MB>(prev + V_OFF + SUB, w, pb, plb, pla, xa, ones, ninf, lm, lane);
+        region_qk_exp<MB, true>(cur + K_OFF, prev + V_OFF + SUB, w, xa, xb, pb, ring, lane);
+        bool grow = region_pv_max<MB, false>(prev + V_OFF + SUB, cur + K_OFF + SUB, w, pb, plb, pla, xa, ones, ninf, lm, ring, lane);
         if (!live) break;
         // (where the exponents change after region 2 has turned the late row block's into
         //  probabilities, those are redone)
@@ -863,8 +869,8 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             late_probabilities<MB>(xa, pla);
         }
         // odd sub-tile of stage k
-        region_qk_exp<MB>(cur + K_OFF + SUB, w, xb, xa, pb, lane);
-        grow = region_pv_max<MB>(cur + V_OFF, w, pb, pla, plb, xb, ones, ninf, lm, lane);
+        region_qk_exp<MB, false>(cur + K_OFF + SUB, cur + V_OFF, w, xb, xa, pb, ring, lane);
+        grow = region_pv_max<MB, true>(cur + V_OFF, nullptr, w, pb, pla, plb, xb, ones, ninf, lm, ring, lane);
         if (t0 + 2 * AT_SUB > sr.P) {
             grow = apply_tree_mask<MB>(xb, w, lm, lane, t0 + AT_SUB, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
             late_probabilities<MB>(xb, plb);
