@@ -314,21 +314,24 @@ __device__ __forceinline__ bf16x8 load_k_operand(const unsigned char* Ks, int g,
 }
 // V^T operand of dim block db through the LDS transpose read: a 16-lane group turns the
 // 4-token x 16-dim block (tokens 16c + 4lg .. +3, dims 16db .. +15) into "lane = dim, 4 tokens".
+// (half c = tokens 16c .. 16c + 15 of the sub-tile: one transpose read, elements 4c .. 4c + 3)
+template <int C>
+__device__ __forceinline__ void load_v_half(bf16x8& va, const unsigned char* Vs, int db, int l16, int lg) {
+    const int row = 16 * C + 4 * lg + (l16 >> 2);
+    const int seg = db ^ (row & 7);
+    const unsigned char* ptr = Vs + row * AT_ROW_BYTES + seg * 32 + 8 * (l16 & 3);
+    const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (short4_t __attribute__((address_space(3)))*)(ptr));
+    const bf16x4 r4 = __builtin_bit_cast(bf16x4, r);
+    va[4 * C + 0] = r4[0];
+    va[4 * C + 1] = r4[1];
+    va[4 * C + 2] = r4[2];
+    va[4 * C + 3] = r4[3];
+}
 __device__ __forceinline__ bf16x8 load_v_operand(const unsigned char* Vs, int db, int l16, int lg) {
     bf16x8 va;
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const int row = 16 * c + 4 * lg + (l16 >> 2);
-        const int seg = db ^ (row & 7);
-        const unsigned char* ptr = Vs + row * AT_ROW_BYTES + seg * 32 + 8 * (l16 & 3);
-        const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (short4_t __attribute__((address_space(3)))*)(ptr));
-        const bf16x4 r4 = __builtin_bit_cast(bf16x4, r);
-        va[4 * c + 0] = r4[0];
-        va[4 * c + 1] = r4[1];
-        va[4 * c + 2] = r4[2];
-        va[4 * c + 3] = r4[3];
-    }
+    load_v_half<0>(va, Vs, db, l16, lg);
+    load_v_half<1>(va, Vs, db, l16, lg);
     return va;
 }
 
@@ -351,7 +354,14 @@ __device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ 
                                               uintx4 (&pb)[MB], bf16x8 (&ring)[4], int lane) {
     constexpr int E = rows_early<MB>();
     const int l16 = lane & 15, lg = lane >> 4;
-    float e0[E], e1[E];         // exponentials waiting to be packed (a pair is packed one group later)
+    constexpr bool LATE = E < MB;
+    constexpr int H = (E + 1) / 2;
+    // Exponentials waiting to be packed.  Pair p = groups 2p (-> e0[p & 1]) and 2p + 1 (-> e1).
+    // With a late row block its slots do the packing, two per slot so that no slot holds more
+    // than 8 cycles of vector work: rows < H of pair p in group 2p + 1, the others in group
+    // 2p + 2 (hence two copies of e0).  Without one, a pair is packed next to the exponential
+    // one group later.
+    float e0[2][E], e1[E];
     if constexpr (FIRST) {
         ring[0] = load_k_operand(Ks, 0, l16, lg);
         ring[1] = load_k_operand(Ks, 1, l16, lg);
@@ -367,16 +377,25 @@ __device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ 
             if constexpr (ds == 0) mfma_x_first<q_reg<MB>(rb, 0), guard>(xn[rb][c], ring[g & 3], w.negm[rb]);
             else mfma_x_next<q_reg<MB>(rb, ds), guard>(xn[rb][c], ring[g & 3]);
             if constexpr (rb < E) {
-                if constexpr ((g & 1) == 0 && g >= 2) pb[rb][(g - 2) >> 1] = pack_bf16(e0[rb], e1[rb]);
+                if constexpr (!LATE && (g & 1) == 0 && g >= 2)
+                    pb[rb][(g - 2) >> 1] = pack_bf16(e0[((g - 2) >> 1) & 1][rb], e1[rb]);
                 const float pe = __builtin_amdgcn_exp2f(xc[rb][c][ds]);
                 if constexpr (g & 1) e1[rb] = pe;
-                else e0[rb] = pe;
+                else e0[(g >> 1) & 1][rb] = pe;
+            } else if constexpr (g & 1) {           // late slot of group 2p + 1: rows < H of pair p
+                constexpr int pr = g >> 1;
+#pragma unroll
+                for (int r = 0; r < H; ++r) pb[r][pr] = pack_bf16(e0[pr & 1][r], e1[r]);
+            } else if constexpr (g >= 2) {          // late slot of group 2p + 2: the other rows of pair p
+                constexpr int pr = (g - 2) >> 1;
+#pragma unroll
+                for (int r = H; r < E; ++r) pb[r][pr] = pack_bf16(e0[pr & 1][r], e1[r]);
             }
             __builtin_amdgcn_sched_barrier(0);
         });
     });
 #pragma unroll
-    for (int rb = 0; rb < E; ++rb) pb[rb][3] = pack_bf16(e0[rb], e1[rb]);
+    for (int rb = LATE ? H : 0; rb < E; ++rb) pb[rb][3] = pack_bf16(e0[1][rb], e1[rb]);
     __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -413,25 +432,38 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
     float le0 = 0.f, le1 = 0.f;
     static_for<0, 8>([&](auto db_) {
         GRAFT_CONST(db, db_);
-        if constexpr (db + 2 < 8) ring[(db + 2) & 3] = load_v_operand(Vs, db + 2, l16, lg);
-        else if constexpr (!LAST) ring[(db + 2) & 3] = load_k_operand(Knext, db + 2 - 8, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
             if constexpr (rb < E) mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(ring[db & 3], pb[rb]);
             else mfma_o<o_reg(rb, db), (db == 0 && rb == 0)>(ring[db & 3], pl_cur);
-            if constexpr (db < 4) {          // two exponents per slot: 4 slots cover the row block's 8
-                const float a = xn[rb][db >> 1][2 * (db & 1)], b = xn[rb][db >> 1][2 * (db & 1) + 1];
-                // (the three-operand form also for the first pair: a plain two-operand
-                // maximum would first canonicalise both inputs, two more instructions)
-                lm[rb] = __builtin_fmaxf(__builtin_fmaxf(db == 0 ? ninf : lm[rb], a), b);
-            } else if constexpr (INLOOP && rb <= 1) {
-                // late row block: element 2 (db - 4) + rb of its 8; a pair is packed in the slot
-                // after its second exponential
-                constexpr int e = 2 * (db - 4) + rb;
+            // The slot's vector work, at most 8 cycles of it where the slots suffice.
+            // LDS reads of the operand two groups ahead: one half in each of the first two slots.
+            if constexpr (rb == 0) {
+                if constexpr (db + 2 < 8) load_v_half<0>(ring[(db + 2) & 3], Vs, db + 2, l16, lg);
+                else if constexpr (!LAST) ring[(db + 2) & 3] = load_k_operand(Knext, db + 2 - 8, l16, lg);
+            }
+            if constexpr (rb == (MB > 1 ? 1 : 0) && db + 2 < 8) load_v_half<1>(ring[(db + 2) & 3], Vs, db + 2, l16, lg);
+            if constexpr (db < 4) {
+                // maximum scan, two exponents of one row block per instruction; slot 0 is left
+                // to the LDS read where there are five slots (row blocks 0 and 1 go to slots 1, 2)
+                static_for<0, MB>([&](auto r_) {
+                    GRAFT_CONST(r, r_);
+                    constexpr int slot = MB == 5 ? (r == 0 ? 1 : (r == 1 ? 2 : r)) : r;
+                    if constexpr (slot == rb) {
+                        const float a = xn[r][db >> 1][2 * (db & 1)], b = xn[r][db >> 1][2 * (db & 1) + 1];
+                        // (the three-operand form also for the first pair: a plain two-operand
+                        // maximum would first canonicalise both inputs, two more instructions)
+                        lm[r] = __builtin_fmaxf(__builtin_fmaxf(db == 0 ? ninf : lm[r], a), b);
+                    }
+                });
+            } else if constexpr (INLOOP && (rb == MB - 3 || rb == MB - 2)) {
+                // late row block: element 2 (db - 4) + {0, 1} of its 8; the pair is packed in
+                // the slot after its second exponential
+                constexpr int e = 2 * (db - 4) + (rb - (MB - 3));
                 const float pe = __builtin_amdgcn_exp2f(xn[MB - 1][e >> 2][e & 3]);
-                if constexpr (rb == 0) le0 = pe;
+                if constexpr (rb == MB - 3) le0 = pe;
                 else le1 = pe;
-            } else if constexpr (INLOOP && rb == 2) {
+            } else if constexpr (INLOOP && rb == MB - 1) {
                 pl_next[db - 4] = pack_bf16(le0, le1);
                 // (pinned here: the caller overwrites pl_next on some paths, and the compiler
                 //  would otherwise move these exponentials to the paths that do not)
