@@ -1021,11 +1021,14 @@ __device__ __forceinline__ void combine_tiles(const float* otile, const float* m
     }
 }
 
-__global__ __launch_bounds__(AT_THREADS) void tree_attn_combine_kernel(AttnParams p) {
+// The host picks the workgroup size (CB_MAX_WAVES wavefronts at most) so that the workgroups
+// come out as a whole number of rounds over the compute units where possible.
+constexpr int CB_MAX_WAVES = 8;
+__global__ __launch_bounds__(64 * CB_MAX_WAVES) void tree_attn_combine_kernel(AttnParams p) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, lg = lane >> 4;
     const int n_blk = p.R_pad >> 4;                                           // 16-row blocks per (b, g)
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * AT_WAVES + wave;  // over B*Hkv*n_blk*8
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;   // over B*Hkv*n_blk*8
     const int64_t n_tiles = static_cast<int64_t>(p.B) * p.Hkv * n_blk * (AT_D / 16);
     if (tile >= n_tiles) return;
     const int db = static_cast<int>(tile & 7);
@@ -1338,8 +1341,13 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     }
     int32_t rc = check_launch();
     if (rc != GRAFT_OK) return rc;
+    // one wavefront per output tile; as many per workgroup as make the workgroups one round
+    // (or, capped, a few whole rounds) over the compute units
     const int64_t n_tiles = static_cast<int64_t>(B) * Hkv * (pl.r_pad / 16) * (AT_D / 16);
-    hipLaunchKernelGGL(tree_attn_combine_kernel, dim3(static_cast<unsigned>((n_tiles + AT_WAVES - 1) / AT_WAVES)),
-                       dim3(AT_THREADS), 0, s, p);
+    const int64_t cus = device_compute_units();
+    int64_t wpw = (n_tiles + cus - 1) / cus;
+    wpw = wpw < 1 ? 1 : (wpw > CB_MAX_WAVES ? CB_MAX_WAVES : wpw);
+    hipLaunchKernelGGL(tree_attn_combine_kernel, dim3(static_cast<unsigned>((n_tiles + wpw - 1) / wpw)),
+                       dim3(static_cast<unsigned>(64 * wpw)), 0, s, p);
     return check_launch();
 }

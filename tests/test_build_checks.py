@@ -62,11 +62,11 @@ def test_unknown_predecessor_after_a_label():
 
 
 def test_compiler_use_of_a_hand_managed_accvgpr():
-    # 48 * MB = 96 registers are hand-managed in the MB = 2 kernel
-    bad = b.check_attention_asm(_asm(FILL + "\n\tv_accvgpr_write_b32 a95, v1\n" + FILL))
+    # 48 * MB + 4 * min(MB, 4) = 104 registers are hand-managed in the MB = 2 kernel
+    bad = b.check_attention_asm(_asm(FILL + "\n\tv_accvgpr_write_b32 a103, v1\n" + FILL))
     assert len(bad) == 1 and "AccVGPR" in bad[0]
     assert b.check_attention_asm(_asm(FILL + "\n\tds_read_b32 a17, v1\n" + FILL))
-    assert b.check_attention_asm(_asm(FILL + "\n\tv_accvgpr_write_b32 a96, v1\n" + FILL)) == []
+    assert b.check_attention_asm(_asm(FILL + "\n\tv_accvgpr_write_b32 a104, v1\n" + FILL)) == []
     inside = "\t;;#ASMSTART\n\tv_accvgpr_write_b32 a[5], v1\n\t;;#ASMEND"
     assert b.check_attention_asm(_asm(FILL + "\n" + inside)) == []
 
