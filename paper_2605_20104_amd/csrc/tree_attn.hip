@@ -75,8 +75,9 @@ struct AttnParams {
     const int32_t* prefix_len;
     const int32_t* n_nodes;
     const u64* mask;
-    float* ws_o;        // [B][Hkv][splits][R_pad/16][D/16] tiles of 1 KB: [lane][4], lane = MFMA accumulator lane
-    float* ws_ml;       // [B][Hkv][splits][R_pad][2]  (max in log2 units, sum)
+    unsigned short* ws_o;   // fp16 [B][Hkv][splits][R_pad/16][D/32] blocks of 1 KB: [lane][2][4], lane = MFMA
+                            // accumulator lane, two adjacent 16-dim tiles per block
+    float* ws_ml;       // [B][Hkv][splits][R_pad][4]  (max in log2 units, sum, scale of the stored row, 0)
     int64_t page_stride, token_stride, head_stride;
     int32_t max_pages, B, K_max, Hq, Hkv, G, R, R_pad, n_splits, n_row_tiles;
     int32_t g_magic;    // ceil(2^16 / G): r / G == (r * g_magic) >> 16 for r < 4096, G <= 16
@@ -957,65 +958,92 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     }
     GRAFT_MFMA_SETTLE();
 
-    // ---- partial results: unnormalised O, reference max (log2 units), row sum.  O is written
-    //      as the accumulator tiles lie in the registers (16 rows x 16 dims, 16 bytes per lane):
-    //      every store instruction then fills 1 KB of consecutive addresses.
+    // ---- partial results.  Per row and split: the reference max m (log2 units), the row sum l
+    //      and O / l, which is a convex combination of V rows, stored as fp16 after an exact
+    //      scaling by a power of two 2^-e that brings the row's largest magnitude into
+    //      [0.5, 1): eleven significant bits relative to the row's largest entry, eight times
+    //      finer than the bf16 rounding of the final output, at half the bytes of fp32 for the
+    //      round trip through memory that the splits cost.  The rows are written as the
+    //      accumulator tiles lie in the registers (two 16 x 16 tiles side by side, 16 bytes per
+    //      lane), so that every store instruction fills 1 KB of consecutive addresses.
+    typedef float floatx2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
     const size_t part = ((static_cast<size_t>(b) * p.Hkv + g) * p.n_splits + split) * p.R_pad;
     static_for<0, MB>([&](auto rb_) {
         GRAFT_CONST(rb, rb_);
         const int r0 = r_base + rb * 16;                          // first row of this 16-row block
-        float* op = p.ws_o + (part + r0) * AT_D + 4 * lane;
-        static_for<0, 8>([&](auto db_) {
-            GRAFT_CONST(db, db_);
-            floatx4 t;
-            t[0] = acc_get<o_reg(rb, db) + 0>();
-            t[1] = acc_get<o_reg(rb, db) + 1>();
-            t[2] = acc_get<o_reg(rb, db) + 2>();
-            t[3] = acc_get<o_reg(rb, db) + 3>();
-            *reinterpret_cast<floatx4*>(op + 256 * db) = t;
+        float l;
+        if constexpr (rb >= L_IN_ACC) l = w.lsum_v[0];
+        else l = acc_get<l_reg<MB>(rb)>();
+        const float inv_l = l > 0.f ? 1.0f / l : 0.f;
+        float ov[32];
+        static_for<0, 32>([&](auto k_) {
+            GRAFT_CONST(k, k_);
+            ov[k] = acc_get<o_reg(rb, 0) + k>();
         });
-        if (lg == 0) {
-            float* ml = p.ws_ml + (part + r0 + l16) * 2;
-            ml[0] = w.m_ref(rb);
-            if constexpr (rb >= L_IN_ACC) ml[1] = w.lsum_v[0];
-            else ml[1] = acc_get<l_reg<MB>(rb)>();
-        }
+        float amax = 0.f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) amax = fmaxf(amax, fabsf(ov[k]));
+        amax = fmaxf(amax, __shfl_xor(amax, 16));
+        amax = fmaxf(amax, __shfl_xor(amax, 32));                 // the row's, same in its four lanes
+        // biased exponent of the normalised row maximum, kept where 2^e and 2^-e are normal numbers
+        // (a zero row, or values at the ends of the fp32 range, keep a scale they can live with)
+        int ex = static_cast<int>((__float_as_uint(amax * inv_l) >> 23) & 0xffu);
+        ex = ex < 2 ? 126 : (ex > 252 ? 252 : ex);
+        const float pow2e = __uint_as_float(static_cast<unsigned>(ex + 1) << 23);      // 2^(ex - 126)
+        const float f = inv_l * __uint_as_float(static_cast<unsigned>(253 - ex) << 23);  // 2^-(ex - 126) / l
+        unsigned short* op = p.ws_o + (part + r0) * AT_D + 8 * lane;
+        static_for<0, 4>([&](auto dp_) {
+            GRAFT_CONST(dp, dp_);
+            uintx4 t;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                t[k] = __builtin_bit_cast(unsigned, __builtin_convertvector(
+                           floatx2{ov[8 * dp + 2 * k] * f, ov[8 * dp + 2 * k + 1] * f}, halfx2));
+            *reinterpret_cast<uintx4*>(op + 512 * dp) = t;
+        });
+        if (lg == 0)
+            *reinterpret_cast<floatx4*>(p.ws_ml + (part + r0 + l16) * 4) = floatx4{w.m_ref(rb), l, pow2e, 0.f};
     });
 }
 
-// Merge the splits of one 16-row x 16-dim output tile: out = sum_s w_s O_s / sum_s w_s l_s with
-// w_s = 2^(m_s - max m).  One wavefront per tile; lane (l16, lg) owns row l16, dims 4 lg .. +3,
-// exactly the 16 bytes it holds of every split's partial tile, so a split is one 1 KB read.
-// U splits are read per step with all their loads in flight (no branch in between: a split
-// without keys has weight 0 and a zero partial tile); the maximum is a running one, and what
+// Merge the splits of two adjacent 16-row x 16-dim output tiles:
+// out = sum_s w_s l_s 2^e_s o_s / sum_s w_s l_s with w_s = 2^(m_s - max m), o_s the stored
+// fp16 rows.  One wavefront per tile pair; lane (l16, lg) owns row l16, dims 4 lg .. +3 of
+// both tiles, exactly the 16 bytes it wrote of every split's block, so a split is one 1 KB
+// read.  U splits are read per step with all their loads in flight (no branch in between: a
+// split without keys has weight 0 and a zero block); the maximum is a running one, and what
 // has been summed is rescaled when a later step raises it.
 template <int U>
-__device__ __forceinline__ void combine_tiles(const float* otile, const float* mlrow, size_t o_stride,
-                                              size_t ml_stride, int ns, floatx4& acc, float& den) {
+__device__ __forceinline__ void combine_tiles(const unsigned short* otile, const float* mlrow, size_t o_stride,
+                                              size_t ml_stride, int ns, float (&acc)[8], float& den) {
+    typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
     float m_run = -INFINITY;
     for (int s0 = 0; s0 < ns; s0 += U) {
-        floatx4 ov[U];
-        float2 ml[U];
+        uintx4 ov[U];
+        floatx4 ml[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int sc = (s0 + u) < ns ? (s0 + u) : (ns - 1);
-            ov[u] = *reinterpret_cast<const floatx4*>(otile + sc * o_stride);
-            ml[u] = *reinterpret_cast<const float2*>(mlrow + sc * ml_stride);
+            ov[u] = *reinterpret_cast<const uintx4*>(otile + sc * o_stride);
+            ml[u] = *reinterpret_cast<const floatx4*>(mlrow + sc * ml_stride);
         }
         float m_new = m_run;
 #pragma unroll
-        for (int u = 0; u < U; ++u) m_new = fmaxf(m_new, ml[u].x);       // a repeated last split changes nothing
+        for (int u = 0; u < U; ++u) m_new = fmaxf(m_new, ml[u][0]);      // a repeated last split changes nothing
         const float keep = m_run > -INFINITY ? __builtin_amdgcn_exp2f(m_run - m_new) : 0.f;
         den *= keep;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] *= keep;
+        for (int e = 0; e < 8; ++e) acc[e] *= keep;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool on = (s0 + u) < ns && ml[u].x > -INFINITY;
-            const float wu = on ? __builtin_amdgcn_exp2f(ml[u].x - m_new) : 0.f;
-            den += wu * ml[u].y;
+            const bool on = (s0 + u) < ns && ml[u][0] > -INFINITY;
+            const float wl = on ? __builtin_amdgcn_exp2f(ml[u][0] - m_new) * ml[u][1] : 0.f;
+            den += wl;
+            const float wu = wl * ml[u][2];
+            const halfx8 h = __builtin_bit_cast(halfx8, ov[u]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] += wu * ov[u][e];
+            for (int e = 0; e < 8; ++e) acc[e] += wu * static_cast<float>(h[e]);
         }
         m_run = m_new;
     }
@@ -1028,26 +1056,26 @@ __global__ __launch_bounds__(64 * CB_MAX_WAVES) void tree_attn_combine_kernel(At
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, lg = lane >> 4;
     const int n_blk = p.R_pad >> 4;                                           // 16-row blocks per (b, g)
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;   // over B*Hkv*n_blk*8
-    const int64_t n_tiles = static_cast<int64_t>(p.B) * p.Hkv * n_blk * (AT_D / 16);
+    const int64_t tile = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;   // over B*Hkv*n_blk*4
+    const int64_t n_tiles = static_cast<int64_t>(p.B) * p.Hkv * n_blk * (AT_D / 32);
     if (tile >= n_tiles) return;
-    const int db = static_cast<int>(tile & 7);
-    const int blk = static_cast<int>((tile >> 3) % n_blk);
-    const int64_t bg = (tile >> 3) / n_blk;                                   // b * Hkv + g
+    const int dp = static_cast<int>(tile & 3);                                // dims 32 dp .. 32 dp + 31
+    const int blk = static_cast<int>((tile >> 2) % n_blk);
+    const int64_t bg = (tile >> 2) / n_blk;                                   // b * Hkv + g
     const int g = static_cast<int>(bg % p.Hkv), b = static_cast<int>(bg / p.Hkv);
     const int r = blk * 16 + l16;
     if (r >= p.R) return;                                                      // padding rows of the tile
     int n = p.n_nodes[b];                                                      // needed only at the end
     const int i = (r * p.g_magic) >> 16, hl = r - i * p.G;                     // i = r / G
     unsigned short* outp = static_cast<unsigned short*>(p.out) +
-        ((static_cast<int64_t>(b) * p.K_max + i) * p.Hq + g * p.G + hl) * AT_D + 16 * db + 4 * lg;
+        ((static_cast<int64_t>(b) * p.K_max + i) * p.Hq + g * p.G + hl) * AT_D + 32 * dp + 4 * lg;
     const int ns = p.n_splits;
     const size_t base = static_cast<size_t>(bg) * ns * p.R_pad + blk * 16;     // row index of split 0
-    const float* mlrow = p.ws_ml + (base + l16) * 2;
-    const size_t ml_stride = static_cast<size_t>(p.R_pad) * 2;
-    const float* otile = p.ws_o + base * AT_D + 256 * db + 4 * lane;
+    const float* mlrow = p.ws_ml + (base + l16) * 4;
+    const size_t ml_stride = static_cast<size_t>(p.R_pad) * 4;
+    const unsigned short* otile = p.ws_o + base * AT_D + 512 * dp + 8 * lane;
     const size_t o_stride = static_cast<size_t>(p.R_pad) * AT_D;
-    floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float den = 0.f;
     if (ns >= 16) combine_tiles<16>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
     else if (ns >= 8) combine_tiles<8>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
@@ -1055,10 +1083,13 @@ __global__ __launch_bounds__(64 * CB_MAX_WAVES) void tree_attn_combine_kernel(At
     else combine_tiles<2>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
     if (n < 1 || n > p.K_max) n = 0;
     const float inv = den > 0.f ? 1.0f / den : 0.f;
-    unsigned o01 = float_to_bf16_bits(acc[0] * inv) | (float_to_bf16_bits(acc[1] * inv) << 16);
-    unsigned o23 = float_to_bf16_bits(acc[2] * inv) | (float_to_bf16_bits(acc[3] * inv) << 16);
-    if (i >= n) o01 = o23 = 0u;              // rows of absent nodes are zeros whatever their Q rows held
-    *reinterpret_cast<uint2*>(outp) = uint2{o01, o23};
+    unsigned o[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        o[k] = float_to_bf16_bits(acc[2 * k] * inv) | (float_to_bf16_bits(acc[2 * k + 1] * inv) << 16);
+    if (i >= n) o[0] = o[1] = o[2] = o[3] = 0u;   // rows of absent nodes are zeros whatever their Q rows held
+    *reinterpret_cast<uint2*>(outp) = uint2{o[0], o[1]};          // dims 32 dp + 4 lg .. +3
+    *reinterpret_cast<uint2*>(outp + 16) = uint2{o[2], o[3]};     // dims 32 dp + 16 + 4 lg .. +3
 }
 
 // ---------------------------------------------------------------------------
@@ -1240,8 +1271,8 @@ static AttnPlan make_plan(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
     }
     pl.r_pad = pl.n_row_tiles * pl.mb * rows_per_mb;
     const size_t rows = static_cast<size_t>(B) * Hkv * pl.n_splits * pl.r_pad;
-    pl.ws_o_bytes = rows * AT_D * sizeof(float);
-    pl.ws_bytes = pl.ws_o_bytes + rows * 2 * sizeof(float);
+    pl.ws_o_bytes = rows * AT_D * sizeof(unsigned short);       // fp16 rows
+    pl.ws_bytes = pl.ws_o_bytes + rows * 4 * sizeof(float);
     return pl;
 }
 
@@ -1328,7 +1359,7 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     }
 
     p.R_pad = pl.r_pad; p.n_splits = pl.n_splits; p.n_row_tiles = pl.n_row_tiles;
-    p.ws_o = static_cast<float*>(workspace);
+    p.ws_o = static_cast<unsigned short*>(workspace);
     p.ws_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + pl.ws_o_bytes);
     const int64_t n_units = static_cast<int64_t>(B) * Hkv * pl.n_splits;
     dim3 grid(static_cast<unsigned>(((n_units + 7) / 8) * 8 * pl.n_row_tiles));
@@ -1343,7 +1374,7 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     if (rc != GRAFT_OK) return rc;
     // one wavefront per output tile; as many per workgroup as make the workgroups one round
     // (or, capped, a few whole rounds) over the compute units
-    const int64_t n_tiles = static_cast<int64_t>(B) * Hkv * (pl.r_pad / 16) * (AT_D / 16);
+    const int64_t n_tiles = static_cast<int64_t>(B) * Hkv * (pl.r_pad / 16) * (AT_D / 32);
     const int64_t cus = device_compute_units();
     int64_t wpw = (n_tiles + cus - 1) / cus;
     wpw = wpw < 1 ? 1 : (wpw > CB_MAX_WAVES ? CB_MAX_WAVES : wpw);
