@@ -1009,78 +1009,99 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
 
 // Merge the splits of two adjacent 16-row x 16-dim output tiles:
 // out = sum_s w_s l_s 2^e_s o_s / sum_s w_s l_s with w_s = 2^(m_s - max m), o_s the stored
-// fp16 rows.  One wavefront per tile pair; lane (l16, lg) owns row l16, dims 4 lg .. +3 of
-// both tiles, exactly the 16 bytes it wrote of every split's block, so a split is one 1 KB
-// read.  U splits are read per step with all their loads in flight (no branch in between: a
-// split without keys has weight 0 and a zero block); the maximum is a running one, and what
-// has been summed is rescaled when a later step raises it.
+// fp16 rows.  Lane (l16, lg) owns row l16, dims 4 lg .. +3 of both tiles, exactly the 16 bytes
+// it wrote of every split's block, so a split is one 1 KB read per wavefront.  The kernel is
+// a chain of memory round trips, not a stream, so a wavefront takes at most U splits (U = 2,
+// 4, 8 or 16, the smallest that covers them: registers, and with them the wavefronts in
+// flight, go with U) and has all their loads in flight at once (a split without keys has
+// weight 0 and a zero block); with more than 16 splits, up to four wavefronts share a tile
+// pair and the first of them merges their sums through LDS.
+constexpr int CB_MAX_SPLITS = 16;
+constexpr int CB_MAX_WAVES = 8;          // per workgroup; the host picks a multiple of the wavefronts per tile pair
+
 template <int U>
-__device__ __forceinline__ void combine_tiles(const unsigned short* otile, const float* mlrow, size_t o_stride,
-                                              size_t ml_stride, int ns, float (&acc)[8], float& den) {
+__global__ __launch_bounds__(64 * CB_MAX_WAVES) void tree_attn_combine_kernel(AttnParams p, int32_t n_tiles, int32_t wpt) {
     typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
-    float m_run = -INFINITY;
-    for (int s0 = 0; s0 < ns; s0 += U) {
-        uintx4 ov[U];
-        floatx4 ml[U];
+    constexpr int CB_SPLITS = U;
+    // (m, den, acc[8]) per lane of the helper wavefronts (only U = 16 has helpers)
+    __shared__ float xch[U == CB_MAX_SPLITS ? CB_MAX_WAVES : 1][10][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, lg = lane >> 4;
+    const int n_blk = p.R_pad >> 4;                                           // 16-row blocks per (b, g)
+    const int tiles_per_wg = (blockDim.x >> 6) / wpt;
+    const int tile = static_cast<int>(blockIdx.x) * tiles_per_wg + wave / wpt;   // over B*Hkv*n_blk*4
+    const int part_i = wave % wpt;                                            // which CB_SPLITS splits
+    const int dp = tile & 3;                                                  // dims 32 dp .. 32 dp + 31
+    const int blk = (tile >> 2) % n_blk;
+    const int bg = (tile >> 2) / n_blk;                                       // b * Hkv + g
+    const int g = bg % p.Hkv, b = bg / p.Hkv;
+    const int r = blk * 16 + l16;
+    const bool live = tile < n_tiles && r < p.R;                              // not a padding row or tile
+    const int ns = p.n_splits;
+    const int s0 = part_i * CB_SPLITS;
+
+    float m_run = -INFINITY, den = 0.f;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int n = 0;
+    if (live) {
+        n = p.n_nodes[b];                                                     // needed only at the end
+        const size_t base = static_cast<size_t>(bg) * ns * p.R_pad + blk * 16;     // row index of split 0
+        const float* mlrow = p.ws_ml + (base + l16) * 4;
+        const size_t ml_stride = static_cast<size_t>(p.R_pad) * 4;
+        const unsigned short* otile = p.ws_o + base * AT_D + 512 * dp + 8 * lane;
+        const size_t o_stride = static_cast<size_t>(p.R_pad) * AT_D;
+        uintx4 ov[CB_SPLITS];
+        floatx4 ml[CB_SPLITS];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int sc = (s0 + u) < ns ? (s0 + u) : (ns - 1);
-            ov[u] = *reinterpret_cast<const uintx4*>(otile + sc * o_stride);
-            ml[u] = *reinterpret_cast<const floatx4*>(mlrow + sc * ml_stride);
+        for (int u = 0; u < CB_SPLITS; ++u) {
+            ov[u] = uintx4{0u, 0u, 0u, 0u};
+            ml[u] = floatx4{-INFINITY, 0.f, 0.f, 0.f};
+            if ((s0 + u) < ns) {                                              // uniform: nothing is read twice
+                ov[u] = *reinterpret_cast<const uintx4*>(otile + (s0 + u) * o_stride);
+                ml[u] = *reinterpret_cast<const floatx4*>(mlrow + (s0 + u) * ml_stride);
+            }
         }
-        float m_new = m_run;
 #pragma unroll
-        for (int u = 0; u < U; ++u) m_new = fmaxf(m_new, ml[u][0]);      // a repeated last split changes nothing
-        const float keep = m_run > -INFINITY ? __builtin_amdgcn_exp2f(m_run - m_new) : 0.f;
-        den *= keep;
+        for (int u = 0; u < CB_SPLITS; ++u)
+            if ((s0 + u) < ns) m_run = fmaxf(m_run, ml[u][0]);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] *= keep;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
+        for (int u = 0; u < CB_SPLITS; ++u) {
             const bool on = (s0 + u) < ns && ml[u][0] > -INFINITY;
-            const float wl = on ? __builtin_amdgcn_exp2f(ml[u][0] - m_new) * ml[u][1] : 0.f;
+            const float wl = on ? __builtin_amdgcn_exp2f(ml[u][0] - m_run) * ml[u][1] : 0.f;
             den += wl;
             const float wu = wl * ml[u][2];
             const halfx8 h = __builtin_bit_cast(halfx8, ov[u]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] += wu * static_cast<float>(h[e]);
         }
-        m_run = m_new;
     }
-}
-
-// The host picks the workgroup size (CB_MAX_WAVES wavefronts at most) so that the workgroups
-// come out as a whole number of rounds over the compute units where possible.
-constexpr int CB_MAX_WAVES = 8;
-__global__ __launch_bounds__(64 * CB_MAX_WAVES) void tree_attn_combine_kernel(AttnParams p) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int l16 = lane & 15, lg = lane >> 4;
-    const int n_blk = p.R_pad >> 4;                                           // 16-row blocks per (b, g)
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * (blockDim.x >> 6) + wave;   // over B*Hkv*n_blk*4
-    const int64_t n_tiles = static_cast<int64_t>(p.B) * p.Hkv * n_blk * (AT_D / 32);
-    if (tile >= n_tiles) return;
-    const int dp = static_cast<int>(tile & 3);                                // dims 32 dp .. 32 dp + 31
-    const int blk = static_cast<int>((tile >> 2) % n_blk);
-    const int64_t bg = (tile >> 2) / n_blk;                                   // b * Hkv + g
-    const int g = static_cast<int>(bg % p.Hkv), b = static_cast<int>(bg / p.Hkv);
-    const int r = blk * 16 + l16;
-    if (r >= p.R) return;                                                      // padding rows of the tile
-    int n = p.n_nodes[b];                                                      // needed only at the end
+    if (U == CB_MAX_SPLITS && wpt > 1) {                                      // uniform over the workgroup
+        if (part_i > 0) {
+            xch[wave][0][lane] = m_run;
+            xch[wave][1][lane] = den;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xch[wave][2 + e][lane] = acc[e];
+        }
+        __syncthreads();
+        if (part_i > 0) return;
+        float m_all = m_run;
+        for (int k = 1; k < wpt; ++k) m_all = fmaxf(m_all, xch[wave + k][0][lane]);
+        const float keep = m_run > -INFINITY ? __builtin_amdgcn_exp2f(m_run - m_all) : 0.f;
+        den *= keep;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= keep;
+        for (int k = 1; k < wpt; ++k) {
+            const float mk = xch[wave + k][0][lane];
+            const float wk = mk > -INFINITY ? __builtin_amdgcn_exp2f(mk - m_all) : 0.f;
+            den += wk * xch[wave + k][1][lane];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += wk * xch[wave + k][2 + e][lane];
+        }
+    }
+    if (!live) return;
     const int i = (r * p.g_magic) >> 16, hl = r - i * p.G;                     // i = r / G
     unsigned short* outp = static_cast<unsigned short*>(p.out) +
         ((static_cast<int64_t>(b) * p.K_max + i) * p.Hq + g * p.G + hl) * AT_D + 32 * dp + 4 * lg;
-    const int ns = p.n_splits;
-    const size_t base = static_cast<size_t>(bg) * ns * p.R_pad + blk * 16;     // row index of split 0
-    const float* mlrow = p.ws_ml + (base + l16) * 4;
-    const size_t ml_stride = static_cast<size_t>(p.R_pad) * 4;
-    const unsigned short* otile = p.ws_o + base * AT_D + 512 * dp + 8 * lane;
-    const size_t o_stride = static_cast<size_t>(p.R_pad) * AT_D;
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    float den = 0.f;
-    if (ns >= 16) combine_tiles<16>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
-    else if (ns >= 8) combine_tiles<8>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
-    else if (ns >= 4) combine_tiles<4>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
-    else combine_tiles<2>(otile, mlrow, o_stride, ml_stride, ns, acc, den);
     if (n < 1 || n > p.K_max) n = 0;
     const float inv = den > 0.f ? 1.0f / den : 0.f;
     unsigned o[4];
@@ -1372,13 +1393,23 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     }
     int32_t rc = check_launch();
     if (rc != GRAFT_OK) return rc;
-    // one wavefront per output tile; as many per workgroup as make the workgroups one round
-    // (or, capped, a few whole rounds) over the compute units
+    // wpt wavefronts per tile pair (cb_u splits each); as many tile pairs per workgroup as
+    // make the workgroups one round (or, capped, a few whole rounds) over the compute units
     const int64_t n_tiles = static_cast<int64_t>(B) * Hkv * (pl.r_pad / 16) * (AT_D / 32);
+    if (n_tiles > (1 << 30)) return GRAFT_ERR_SHAPE;
+    const int cb_u = pl.n_splits > 8 ? 16 : (pl.n_splits > 4 ? 8 : (pl.n_splits > 2 ? 4 : 2));
+    const int wpt = (pl.n_splits + cb_u - 1) / cb_u;                       // 1 .. 4
     const int64_t cus = device_compute_units();
-    int64_t wpw = (n_tiles + cus - 1) / cus;
-    wpw = wpw < 1 ? 1 : (wpw > CB_MAX_WAVES ? CB_MAX_WAVES : wpw);
-    hipLaunchKernelGGL(tree_attn_combine_kernel, dim3(static_cast<unsigned>((n_tiles + wpw - 1) / wpw)),
-                       dim3(static_cast<unsigned>(64 * wpw)), 0, s, p);
+    int64_t tpw = (n_tiles + cus - 1) / cus;                               // tile pairs per workgroup
+    const int64_t tpw_max = CB_MAX_WAVES / wpt;
+    tpw = tpw < 1 ? 1 : (tpw > tpw_max ? tpw_max : tpw);
+    const dim3 cgrid(static_cast<unsigned>((n_tiles + tpw - 1) / tpw)), cblock(static_cast<unsigned>(64 * tpw * wpt));
+    const int32_t nt = static_cast<int32_t>(n_tiles);
+    switch (cb_u) {
+        case 2: hipLaunchKernelGGL(tree_attn_combine_kernel<2>, cgrid, cblock, 0, s, p, nt, wpt); break;
+        case 4: hipLaunchKernelGGL(tree_attn_combine_kernel<4>, cgrid, cblock, 0, s, p, nt, wpt); break;
+        case 8: hipLaunchKernelGGL(tree_attn_combine_kernel<8>, cgrid, cblock, 0, s, p, nt, wpt); break;
+        default: hipLaunchKernelGGL(tree_attn_combine_kernel<16>, cgrid, cblock, 0, s, p, nt, wpt); break;
+    }
     return check_launch();
 }
