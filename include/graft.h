@@ -172,7 +172,11 @@ int32_t graft_build_tree_mask(const int32_t* parent, const int32_t* n_nodes, con
  * scale                       softmax scale, normally 1/sqrt(D)
  * dtype                       GRAFT_F32: fp32 storage and arithmetic throughout.
  *                             GRAFT_BF16: bf16 storage, fp32 scores/softmax/accumulation,
- *                             probabilities rounded to bf16 for the P.V product.
+ *                             probabilities rounded to bf16 for the P.V product; where the
+ *                             keys are split over workgroups, each split's normalised
+ *                             partial row passes through memory as fp16 scaled by a power
+ *                             of two to its largest entry (2^-11 of that entry, well inside
+ *                             the bf16 rounding of the result).
  * workspace                   at least graft_tree_attn_workspace_bytes(...) bytes,
  *                             256-byte aligned; contents are scratch.
  *

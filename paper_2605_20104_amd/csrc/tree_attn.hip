@@ -29,15 +29,18 @@
 //               block into "lane = dim, 4 tokens packed".  Row sums: one more
 //               MFMA per row block with an all-ones A operand.
 //       pipeline: over 32-token sub-tiles, MFMAs of one sub-tile interleaved slot
-//               by slot with the exp2 / pack / max work of its neighbours.
+//               by slot with the exp2 / pack / max work of its neighbours; the
+//               MFMA operands are read from LDS two groups ahead, across the
+//               boundary between the two regions of a step.
 //       mask  : only sub-tiles that reach past the prefix take the masked path
 //               (ancestor bits from graft_build_tree_mask); the prefix is dense.
 //       softmax: a row's reference is the maximum of the first sub-tile that gives
 //               it a finite score and is kept while later exponents stay below
 //               2^24; beyond that the wavefront switches to an exact online
 //               softmax loop that rescales the accumulators.
-//     Partials (unnormalised O, reference, sum) go to the workspace; a small
-//     combine kernel merges the splits and writes bf16.
+//     Partials (reference, sum, and O / sum as fp16 rows with a per-row scale)
+//     go to the workspace; a small combine kernel merges the splits and writes
+//     bf16.
 //
 // (2) everything else (fp32 storage, or D = 64): a plain one-workgroup-per-
 //     (node, head) kernel in fp32.  It serves the tiny fp32 configuration and as
