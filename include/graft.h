@@ -175,8 +175,9 @@ int32_t graft_build_tree_mask(const int32_t* parent, const int32_t* n_nodes, con
  *                             probabilities rounded to bf16 for the P.V product; where the
  *                             keys are split over workgroups, each split's normalised
  *                             partial row passes through memory as fp16 scaled by a power
- *                             of two to its largest entry (2^-11 of that entry, well inside
- *                             the bf16 rounding of the result).
+ *                             of two to its largest entry: 11 bits for entries within
+ *                             2^-14 of the row's largest (finer than the bf16 rounding of
+ *                             the result), an absolute 2^-25 of it below that.
  * workspace                   at least graft_tree_attn_workspace_bytes(...) bytes,
  *                             256-byte aligned; contents are scratch.
  *

@@ -197,6 +197,34 @@ def test_scores_that_outgrow_the_reference():
     assert np.abs(got - ref.astype(np.float32)).max() <= 4e-2       # outputs are single V rows of size O(4)
 
 
+@pytest.mark.parametrize("log2_scale", [-100, -20, 40, 100])
+def test_value_magnitudes_across_the_bf16_range(log2_scale):
+    """The splits' partial rows pass through memory as fp16 scaled per row by a power of two:
+    values far outside the fp16 range (V multiplied by 2^-100 .. 2^100, exact in bf16) must come
+    out as accurately as O(1) values, and so must dims whose magnitudes differ by 2^12 within a
+    row (they stay inside fp16's normal range below the row maximum).  Many splits: a long
+    prefix for a batch of one."""
+    w = shape_workload(1, 24, 8, 2, 128, 6000)
+    att = inputs.make_attention_inputs(w, seed=21)
+    v = inputs.bf16_bits_to_f32(att["v_cache"][0]).astype(np.float64)
+    spread = np.exp2(np.linspace(-6, 6, w.D).round())                       # per dim, exact powers of two
+    v = v * spread * np.exp2(float(log2_scale))
+    att["v_cache"] = [inputs.f32_to_bf16_bits(v.astype(np.float32))]
+    rng = np.random.default_rng(21)
+    parent = np.stack([inputs.random_recursive_tree(rng, w.K, 8)])
+    mask = gpu_mask(parent, [w.K], [w.P])
+    got = run_attn(att, "bf16", np.array([w.P], np.int32), np.array([w.K], np.int32), mask, w.Hkv)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
+                           att["block_table"], [w.P], [w.K], parent, w.Hq, w.Hkv, w.D, 16, att["scale"])
+    assert np.isfinite(got).all()
+    # every dim's values share a magnitude: the error of a dim is taken relative to that dim's
+    # largest output (what TOL_BF16 means for O(1) values)
+    unit = np.abs(ref).max(axis=(0, 1, 2), keepdims=True)
+    assert (unit > 0).all()
+    err = (np.abs(got.astype(np.float64) - ref) / unit).max()
+    assert err <= TOL_BF16, "max err relative to the dim's largest output %.3e" % err
+
+
 def test_c2_full_size_all_rows():
     w = inputs.get_workload("c2")
     s = inputs.make_step_inputs(w)
