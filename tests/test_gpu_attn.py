@@ -117,6 +117,18 @@ def test_bf16_capacity_far_beyond_the_length():
     assert np.abs(got - ref.astype(np.float32)).max() <= TOL_BF16
 
 
+@pytest.mark.parametrize("P,Hkv", [(40000, 2), (9000, 1), (2500, 4)])
+def test_bf16_many_splits(P, Hkv):
+    """A long prefix for a single sequence with few KV heads takes the most splits the plan allows
+    (up to 64): the combine step then merges through several wavefronts per tile (more than 16
+    splits), or through its 16-, 8- and 4-split variants.  Sampled rows against the oracle."""
+    w = shape_workload(1, 16, 4 * Hkv, Hkv, 128, P)
+    rng = np.random.default_rng(P)
+    rows = [(0, int(rng.integers(w.K)), int(rng.integers(w.Hq))) for _ in range(24)]
+    rows += [(0, 0, 0), (0, w.K - 1, w.Hq - 1)]
+    check_case(w, seed=P, rows=rows)
+
+
 def test_bf16_token_major_layout_and_deep_chain():
     w = shape_workload(2, 64, 8, 2, 128, 200)
     check_case(w, seed=6, layout="token_major", max_depth=63)
