@@ -96,6 +96,7 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
     __shared__ int32_t tok[AC_THREADS];
     __shared__ int32_t tstar[AC_THREADS];
     __shared__ u64 red[AC_THREADS / 64];
+    __shared__ int32_t best_d;
 
     const int32_t n = n_nodes[b];
     const bool n_ok = n >= 1 && n <= K_max;
@@ -105,6 +106,8 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
     if (n_ok && i < n) bad = (i == 0) ? (p != -1) : (p < 0 || p >= i);
     par[i] = p;
     tok[i] = i < K_max ? tokens[row + i] : -1;
+    // (requested with the other inputs: one trip to memory for all of them)
+    const int32_t ts_given = (!partial && i < K_max) ? target_ids[row + i] : -1;
     const int any_bad = __syncthreads_or(bad ? 1 : 0);
 
     const int32_t width = depth_cap + 1;
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
             }
             target_ids[row + i] = ts;
         } else {
-            ts = target_ids[row + i];
+            ts = ts_given;
         }
     }
     tstar[i] = ts;
@@ -156,6 +159,7 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
         accept_len[b] = d;
         best_node[b] = i;
         status[b] = any_over ? GRAFT_STATUS_PATH_OVERFLOW : 0;
+        best_d = d;
         int32_t k = d;
         for (int32_t j = i; j != -1; j = par[j]) {
             path_b[k] = j;
@@ -163,8 +167,10 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
             --k;
         }
         out_b[d] = ts;
-        for (k = d + 1; k < width; ++k) { path_b[k] = -1; out_b[k] = -1; }
     }
+    __syncthreads();
+    // the padding behind the path: all threads, not one after the other
+    for (int32_t k = best_d + 1 + i; k < width; k += AC_THREADS) { path_b[k] = -1; out_b[k] = -1; }
 }
 
 }  // namespace graft

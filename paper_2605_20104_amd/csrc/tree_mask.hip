@@ -22,6 +22,7 @@ __global__ __launch_bounds__(TM_THREADS) void tree_mask_kernel(
     __shared__ int32_t wave_leaves[TM_THREADS / 64];
 
     const int32_t n = n_nodes[b];
+    const int32_t P = prefix_len[b];          // with the other inputs: one trip to memory for all of them
     const bool n_ok = n >= 1 && n <= K_max;
     const int32_t p = i < K_max ? parent[static_cast<size_t>(b) * K_max + i] : -1;
     bool bad = !n_ok;
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(TM_THREADS) void tree_mask_kernel(
         mask_b[i * GRAFT_MASK_WORDS] = m0;
         mask_b[i * GRAFT_MASK_WORDS + 1] = m1;
         depth[static_cast<size_t>(b) * K_max + i] = d;
-        pos[static_cast<size_t>(b) * K_max + i] = i < n ? prefix_len[b] + d : -1;
+        pos[static_cast<size_t>(b) * K_max + i] = i < n ? P + d : -1;
     }
 
     int overflow = 0;
