@@ -842,9 +842,9 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             acc_set<32 * rb + k>(0.0f);
         });
     });
-    // Q must have landed before the loop: a pending compiler-tracked load would make every
-    // iteration drain the vector memory counter (and the stages in flight with it).
-    GRAFT_WAIT_VMCNT(0);
+    // Every load the compiler tracks (lengths, Q, masks, table) was consumed above, before the
+    // first transfer was issued; only the transfers of stages 0 and 1 are in flight, and the
+    // first advance() waits for stage 0 alone.
     GRAFT_MFMA_SETTLE();
 
     uintx4 ones_bits;
