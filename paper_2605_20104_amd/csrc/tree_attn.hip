@@ -168,9 +168,11 @@ __device__ __forceinline__ void lds_barrier() {
 // Hazards handled by construction: no vector ALU, LDS or memory instruction touches an MFMA
 // result within 16 instructions of the MFMA (the pipeline regions are far apart and explicit
 // s_nop guards the other places), dependent MFMAs on one accumulator are at least two
-// instructions apart, AccVGPR writes are followed by s_nop before an MFMA reads them, every
-// MFMA asm begins with s_nop 1 (a vector ALU write of one of its VGPR sources may sit right
-// in front of it), and constants used as MFMA sources are made opaque to the compiler.
+// instructions apart, AccVGPR writes are followed by s_nop before an MFMA reads them, an MFMA
+// that may have a vector ALU write of one of its VGPR sources right in front of it (the first
+// of a pipeline region, all of the slow path) begins with s_nop 1, and constants used as MFMA
+// sources are made opaque to the compiler.  The build checks the generated assembly for the
+// source-write distance, for compiler use of the hand-managed registers and for spills.
 #define GRAFT_ACC_BLOCK_0 "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15", "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31", "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47"
 #define GRAFT_ACC_BLOCK_1 "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63", "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79", "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95"
 #define GRAFT_ACC_BLOCK_2 "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111", "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127", "a128", "a129", "a130", "a131", "a132", "a133", "a134", "a135", "a136", "a137", "a138", "a139", "a140", "a141", "a142", "a143"
