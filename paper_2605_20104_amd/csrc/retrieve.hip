@@ -5,10 +5,10 @@
 // launch, few dependent memory round trips, and an exact total order on the hits.
 //
 //   1. the query (last n_max tokens of context ++ tail) goes to LDS, reversed;
-//   2. the context passes through LDS in chunks of 8192 tokens (two buffers).  The loads
-//      run four chunks (32 per thread, independent and coalesced) ahead of the scan and
-//      the first four are issued before anything else, so a 32K-token context costs one
-//      exposed memory round trip.  Every thread looks at positions tid, tid+1024, ... of
+//   2. the context passes through LDS in chunks of 16384 tokens (two buffers: 128 KB of the
+//      compute unit's 160).  The loads run two chunks (32 per thread, independent and
+//      coalesced) ahead of the scan and the first two are issued before anything else, so
+//      a 32K-token context costs one exposed memory round trip and two passes of the scan.  Every thread looks at positions tid, tid+1024, ... of
 //      the chunk and, where the token equals the query's last token, walks backwards
 //      through LDS to measure the match length (the previous chunk is still in the
 //      other buffer);
@@ -24,9 +24,9 @@ namespace graft {
 
 constexpr int RT_THREADS = 1024;
 constexpr int RT_WAVES = RT_THREADS / 64;
-constexpr int RT_UNROLL = 8;
+constexpr int RT_UNROLL = 16;
 constexpr int RT_CHUNK = RT_THREADS * RT_UNROLL;      // tokens per LDS buffer
-constexpr int RT_AHEAD = 4;                           // chunks the loads run ahead of the scan
+constexpr int RT_AHEAD = 2;                           // chunks the loads run ahead of the scan
 
 __global__ __launch_bounds__(RT_THREADS) void retrieve_kernel(
     const int32_t* __restrict__ ctx, const int32_t* __restrict__ ctx_len, int32_t L_max,
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(RT_THREADS) void retrieve_kernel(
                     }
                 }
             }
-            if (c + RT_AHEAD < n_chunks) {        // this slot's registers are free: fetch four chunks ahead
+            if (c + RT_AHEAD < n_chunks) {        // this slot's registers are free: fetch RT_AHEAD chunks ahead
 #pragma unroll
                 for (int u = 0; u < RT_UNROLL; ++u) {
                     const int32_t i = (c + RT_AHEAD) * RT_CHUNK + tid + u * RT_THREADS;
