@@ -814,12 +814,21 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         else GRAFT_WAIT_VMCNT(0);
         lds_barrier();
     };
+    // The compute unit's address path takes about 16 cycles per 1 KB transfer, and a wavefront
+    // that issues waits for its turn: four wavefronts issuing their 8 transfers at the same
+    // time hold each other up for about 500 cycles.  So only the first two issue right after
+    // the barrier; the other two issue in the middle of the stage (the target buffer is free
+    // during the whole stage), when the first two are computing.
+    const bool early_wave = wave_u < 2;
+    int next_issue = 0;                          // stages are issued in order, each once
+    auto issue_upto = [&](int s) {
+        while (next_issue <= s && next_issue < n_st) issue_stage(next_issue++);
+    };
     auto advance = [&](int k) {
         arrive(k);
-        if (k + 2 < n_st) issue_stage(k + 2);
+        if (early_wave) issue_upto(k + 2);
     };
-    if (n_st > 0) issue_stage(0);
-    if (n_st > 1) issue_stage(1);
+    issue_upto(1);
 
     // ---- this wavefront's rows: Q' = bf16(Q * scale * log2 e) into AccVGPRs, O^T to zero
     const float c_log2 = p.scale_log2e;
@@ -881,11 +890,8 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     for (int k = 0; k <= n_st; ++k) {
         reserve_acc_registers<MB>();    // nothing of the compiler's may live in the hand-managed AccVGPRs here
         const bool live = k < n_st;
-        // All transfers of stage k + 2 are issued right after the barrier.  The compute unit's
-        // address path takes about 16 cycles per 1 KB transfer, so the four wavefronts hold
-        // each other up for about 500 cycles here; measured alternatives were slower (a
-        // transfer issued while MFMAs are in flight stalls the wavefront for far longer,
-        // whether the transfers are spread over the step or staggered by wavefront).
+        // (transfers of stage k + 2: see advance(); issuing them inside the MFMA regions was
+        //  measured slower, a transfer issued while MFMAs are in flight stalls the wavefront)
         if (live) advance(k);
         const unsigned char* cur = kv[k & (AT_NBUF - 1)];
         const unsigned char* prev = kv[(k - 1) & (AT_NBUF - 1)];
@@ -906,6 +912,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             if (set_references<MB>(lm, w, xa)) { slow = true; j = 2 * k; break; }
             late_probabilities<MB>(xa, pla);
         }
+        if (!early_wave) issue_upto(k + 2);
         // odd sub-tile of stage k
         region_qk_exp<MB, false>(cur + K_OFF + SUB, cur + V_OFF, w, xb, xa, pb, ring, lane);
         grow = region_pv_max<MB, true>(cur + V_OFF, nullptr, w, pb, pla, plb, xb, ones, ninf, lm, ring, lane);
@@ -930,6 +937,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     // ---- slow loop (rare): xa holds the exponents of sub-tile j against the old references and
     //      lm their row maxima.  One sub-tile at a time, exact running max.
     if (slow) {
+        issue_upto((j >> 1) + 2);       // a late-issuing wavefront may have left before its turn
         while (true) {
             reserve_acc_registers<MB>();
             const unsigned char* cur = kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB;
@@ -938,7 +946,10 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             pv_only<MB>(cur + V_OFF, w, pb, ones, lane);
             ++j;
             if (j >= n_sub) break;
-            if ((j & 1) == 0) advance(j >> 1);
+            if ((j & 1) == 0) {
+                advance(j >> 1);
+                issue_upto((j >> 1) + 2);
+            }
             qk_only<MB>(kv[(j >> 1) & (AT_NBUF - 1)] + (j & 1) * SUB + K_OFF, w, xa, lane);
 #pragma unroll
             for (int rb = 0; rb < MB; ++rb) {
