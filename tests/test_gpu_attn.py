@@ -237,6 +237,37 @@ def test_value_magnitudes_across_the_bf16_range(log2_scale):
     assert err <= TOL_BF16, "max err relative to the dim's largest output %.3e" % err
 
 
+def test_scores_that_outgrow_the_reference_in_long_splits():
+    """The same rising and falling scores with many (sequence, head) units, so that every workgroup
+    runs several stages: wavefronts leave the fast path in the middle of their split, at an even or
+    an odd sub-tile, while transfers of later stages are still to be issued."""
+    w = shape_workload(8, 16, 8, 8, 128, 1500)
+    att = inputs.make_attention_inputs(w, seed=14)
+    pages = att["pages_per_seq"]
+    k = inputs.bf16_bits_to_f32(att["k_cache"][0]).copy()
+    q = inputs.bf16_bits_to_f32(att["q"][0]).copy()
+    prefix = np.array([1500, 1484, 1001, 777, 1500, 1203, 690, 1499], np.int32)
+    for b in range(w.B):
+        for lp in range(pages):
+            t = lp * 16 + np.arange(16)
+            # flat for a while, then rising: the reference is outgrown at a different place per sequence
+            ramp = np.maximum(t - (100 + 97 * b), 0) * 0.0153
+            k[att["block_table"][b, lp]] = ramp[None, :, None]
+    q[:] = 1.0
+    q[:, :, 1::2, :] = -1.0                                                  # odd heads: falling scores
+    att["k_cache"] = [inputs.f32_to_bf16_bits(k)]
+    att["q"] = [inputs.f32_to_bf16_bits(q)]
+    rng = np.random.default_rng(14)
+    parent = np.stack([inputs.random_recursive_tree(rng, w.K, 8) for _ in range(w.B)])
+    n_nodes = np.full(w.B, w.K, np.int32)
+    mask = gpu_mask(parent, n_nodes, prefix)
+    got = run_attn(att, "bf16", prefix, n_nodes, mask, w.Hkv)
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
+                           att["block_table"], prefix, n_nodes, parent, w.Hq, w.Hkv, w.D, 16, att["scale"])
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref.astype(np.float32)).max() <= 4e-2       # outputs are single V rows of size O(4)
+
+
 def test_c2_full_size_all_rows():
     w = inputs.get_workload("c2")
     s = inputs.make_step_inputs(w)
