@@ -904,11 +904,11 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         if (!live) break;
         // (where the exponents change after region 2 has turned the late row block's into
         //  probabilities, those are redone)
-        if (t0 + AT_SUB > sr.P) {
+        if (__builtin_expect(t0 + AT_SUB > sr.P, 0)) {
             grow = apply_tree_mask<MB>(xa, w, lm, lane, t0, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
             late_probabilities<MB>(xa, pla);
         }
-        if (grow) {
+        if (__builtin_expect(grow, 0)) {
             if (set_references<MB>(lm, w, xa)) { slow = true; j = 2 * k; break; }
             late_probabilities<MB>(xa, pla);
         }
@@ -916,11 +916,11 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         // odd sub-tile of stage k
         region_qk_exp<MB, false>(cur + K_OFF + SUB, cur + V_OFF, w, xb, xa, pb, ring, lane);
         grow = region_pv_max<MB, true>(cur + V_OFF, nullptr, w, pb, pla, plb, xb, ones, ninf, lm, ring, lane);
-        if (t0 + 2 * AT_SUB > sr.P) {
+        if (__builtin_expect(t0 + 2 * AT_SUB > sr.P, 0)) {
             grow = apply_tree_mask<MB>(xb, w, lm, lane, t0 + AT_SUB, sr.P, sr.n, r_base, p.R, p.g_magic, Ms);
             late_probabilities<MB>(xb, plb);
         }
-        if (grow) {
+        if (__builtin_expect(grow, 0)) {
             if (set_references<MB>(lm, w, xb)) {
                 slow = true;
                 j = 2 * k + 1;
