@@ -347,6 +347,16 @@ __device__ __forceinline__ bf16x8 load_v_operand(const unsigned char* Vs, int db
 // last ("late") row block's probabilities are computed one region earlier, in region 2,
 // whose other vector work (the maximum scan) leaves slots free.
 template <int MB> constexpr int rows_early() { return MB >= 2 ? MB - 1 : MB; }
+// The two pipeline regions share a ring of four MFMA operand buffers.  Operand g of a region
+// (eight per region) lives in ring[g & 3] and is read from LDS read_ahead<MB>() groups before
+// its MFMAs; the last groups of a region read the first operands of the region that follows
+// (K after V after K ...), so the LDS latency never shows at a region's start.  The exception
+// is the first region of a stage (FIRST): the stage is only known to have landed after the
+// barrier in front of it, so it reads its own first operands and the region before it (LAST)
+// reads nothing ahead.
+// How many groups (of MB MFMAs, 16.4 cycles each) an operand is read from LDS ahead of its use.
+// Three (the most the ring allows) was measured 2 % slower than two with three row blocks.
+template <int MB> constexpr int read_ahead() { return 2; }
 
 // Pipeline region 1: the matrix cores compute the exponents of the NEXT sub-tile
 // (X^T = K Q'^T - m_ref into xn) while the vector ALUs turn the CURRENT sub-tile's exponents
@@ -359,6 +369,7 @@ __device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ 
                                               floatx4 (&xn)[MB][2], const floatx4 (&xc)[MB][2],
                                               uintx4 (&pb)[MB], bf16x8 (&ring)[4], int lane) {
     constexpr int E = rows_early<MB>();
+    constexpr int PF = read_ahead<MB>();
     const int l16 = lane & 15, lg = lane >> 4;
     constexpr bool LATE = E < MB;
     constexpr int H = (E + 1) / 2;
@@ -371,12 +382,13 @@ __device__ __forceinline__ void region_qk_exp(const unsigned char* __restrict__ 
     if constexpr (FIRST) {
         ring[0] = load_k_operand(Ks, 0, l16, lg);
         ring[1] = load_k_operand(Ks, 1, l16, lg);
+        if constexpr (PF > 2) ring[2] = load_k_operand(Ks, 2, l16, lg);
     }
     static_for<0, 8>([&](auto g_) {
         GRAFT_CONST(g, g_);
         constexpr int c = g >> 2, ds = g & 3;
-        if constexpr (g + 2 < 8) ring[(g + 2) & 3] = load_k_operand(Ks, g + 2, l16, lg);
-        else ring[(g + 2) & 3] = load_v_operand(Vnext, g + 2 - 8, l16, lg);
+        if constexpr (g + PF < 8) ring[(g + PF) & 3] = load_k_operand(Ks, g + PF, l16, lg);
+        else ring[(g + PF) & 3] = load_v_operand(Vnext, g + PF - 8, l16, lg);
         static_for<0, MB>([&](auto rb_) {
             GRAFT_CONST(rb, rb_);
             constexpr bool guard = (g == 0 && rb == 0);
@@ -432,6 +444,7 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
                                               const floatx4 (&xn)[MB][2], const bf16x8& ones, float ninf,
                                               float (&lm)[MB], bf16x8 (&ring)[4], int lane) {
     constexpr int E = rows_early<MB>();
+    constexpr int PF = read_ahead<MB>();
     constexpr bool LATE = E < MB;
     constexpr bool INLOOP = LATE && MB >= 3;     // three free slots per group are needed
     const int l16 = lane & 15, lg = lane >> 4;
@@ -445,10 +458,10 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
             // The slot's vector work, at most 8 cycles of it where the slots suffice.
             // LDS reads of the operand two groups ahead: one half in each of the first two slots.
             if constexpr (rb == 0) {
-                if constexpr (db + 2 < 8) load_v_half<0>(ring[(db + 2) & 3], Vs, db + 2, l16, lg);
-                else if constexpr (!LAST) ring[(db + 2) & 3] = load_k_operand(Knext, db + 2 - 8, l16, lg);
+                if constexpr (db + PF < 8) load_v_half<0>(ring[(db + PF) & 3], Vs, db + PF, l16, lg);
+                else if constexpr (!LAST) ring[(db + PF) & 3] = load_k_operand(Knext, db + PF - 8, l16, lg);
             }
-            if constexpr (rb == (MB > 1 ? 1 : 0) && db + 2 < 8) load_v_half<1>(ring[(db + 2) & 3], Vs, db + 2, l16, lg);
+            if constexpr (rb == (MB > 1 ? 1 : 0) && db + PF < 8) load_v_half<1>(ring[(db + PF) & 3], Vs, db + PF, l16, lg);
             if constexpr (db < 4) {
                 // maximum scan, two exponents of one row block per instruction; slot 0 is left
                 // to the LDS read where there are five slots (row blocks 0 and 1 go to slots 1, 2)
