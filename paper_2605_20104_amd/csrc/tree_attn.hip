@@ -308,6 +308,8 @@ struct WaveRows {
     floatx4 lsum_v;         // row sums of a fifth row block (the others' are in AccVGPRs)
     float thr[MB];          // an exponent above this needs attention: -inf while the row has no reference
                             // yet, else the lazy bound
+    float thr_min;          // the smallest of thr[]: one compare of the largest new exponent against it
+                            // decides whether any row needs attention (the rows are then looked at one by one)
     __device__ __forceinline__ bool unset(int rb) const { return thr[rb] == -INFINITY; }
     __device__ __forceinline__ float m_ref(int rb) const { return unset(rb) ? -INFINITY : -negm[rb][0]; }
 };
@@ -449,6 +451,7 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
     constexpr bool INLOOP = LATE && MB >= 3;     // three free slots per group are needed
     const int l16 = lane & 15, lg = lane >> 4;
     float le0 = 0.f, le1 = 0.f;
+    unsigned long long above = 0;
     static_for<0, 8>([&](auto db_) {
         GRAFT_CONST(db, db_);
         static_for<0, MB>([&](auto rb_) {
@@ -475,6 +478,17 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
                         lm[r] = __builtin_fmaxf(__builtin_fmaxf(db == 0 ? ninf : lm[r], a), b);
                     }
                 });
+            }
+            if constexpr (db == 4 && rb == (MB >= 4 ? 0 : MB - 1)) {
+                // the scan is complete: one compare for all row blocks, long before the branch on
+                // it at the end of the region (a branch on a fresh vector compare would stall)
+                float lmax = lm[0];
+#pragma unroll
+                for (int r = 1; r < MB; ++r) lmax = __builtin_fmaxf(lmax, lm[r]);
+                above = __builtin_amdgcn_ballot_w64(lmax > w.thr_min);
+                asm volatile("" : "+s"(above));
+            }
+            if constexpr (db < 4) {
             } else if constexpr (INLOOP && (rb == MB - 3 || rb == MB - 2)) {
                 // late row block: element 2 (db - 4) + {0, 1} of its 8; the pair is packed in
                 // the slot after its second exponential
@@ -498,10 +512,7 @@ __device__ __forceinline__ bool region_pv_max(const unsigned char* __restrict__ 
         else if constexpr (rb < E) mfma_rowsum_acc<l_reg<MB>(rb)>(ones, pb[rb]);
         else mfma_rowsum_acc<l_reg<MB>(rb)>(ones, pl_cur);
     });
-    bool grow = false;
-#pragma unroll
-    for (int rb = 0; rb < MB; ++rb) grow = grow || (lm[rb] > w.thr[rb]);
-    const bool any = __builtin_amdgcn_ballot_w64(grow) != 0;
+    const bool any = above != 0;
 #pragma unroll
     for (int rb = 0; rb < E; ++rb) GRAFT_KEEP(pb[rb]);
     GRAFT_KEEP(pl_cur);
@@ -574,6 +585,10 @@ __device__ __forceinline__ bool set_references(float (&lm)[MB], WaveRows<MB>& w,
                 for (int i = 0; i < 4; ++i) x[rb][c][i] -= lm[rb];
         }
     }
+    float tm = w.thr[0];
+#pragma unroll
+    for (int rb = 1; rb < MB; ++rb) tm = fminf(tm, w.thr[rb]);
+    w.thr_min = tm;
     return false;
 }
 
@@ -854,6 +869,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             acc_set_bits<q_reg<MB>(rb, 0) + k>(scale_bf16_pair(qd[rb][k >> 2][k & 3], c_row));
         });
         w.thr[rb] = -INFINITY;
+        w.thr_min = -INFINITY;
         w.negm[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
         if constexpr (rb >= L_IN_ACC) w.lsum_v = floatx4{0.f, 0.f, 0.f, 0.f};
         else
