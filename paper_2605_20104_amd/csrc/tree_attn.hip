@@ -769,6 +769,33 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             tbv[u] = (tid + u * AT_THREADS) < n_pg ? table[pg < last_pg ? pg : last_pg] : 0;
         }
     }
+    // ---- this wavefront's rows: Q' = bf16(Q * scale * log2 e) into AccVGPRs, O^T to zero.  Done
+    //      here, while the table entries are on their way (Q was requested before them and vector
+    //      memory returns in order): some 700 vector instructions that would otherwise sit
+    //      between the first transfers and the first MFMA.
+    const float c_log2 = p.scale_log2e;
+    WaveRows<MB> w;
+    static_for<0, MB>([&](auto rb_) {
+        GRAFT_CONST(rb, rb_);
+        const float c_row = (r_base + rb * 16 + l16) < p.R ? c_log2 : 0.0f;
+        static_for<0, 16>([&](auto k_) {
+            GRAFT_CONST(k, k_);
+            acc_set_bits<q_reg<MB>(rb, 0) + k>(scale_bf16_pair(qd[rb][k >> 2][k & 3], c_row));
+        });
+        w.thr[rb] = -INFINITY;
+        w.thr_min = -INFINITY;
+        w.negm[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (rb >= L_IN_ACC) w.lsum_v = floatx4{0.f, 0.f, 0.f, 0.f};
+        else
+            static_for<0, 4>([&](auto k_) {
+                GRAFT_CONST(k, k_);
+                acc_set<l_reg<MB>(rb) + k>(0.0f);
+            });
+        static_for<0, 32>([&](auto k_) {
+            GRAFT_CONST(k, k_);
+            acc_set<32 * rb + k>(0.0f);
+        });
+    });
     // the first pipeline step multiplies zero probabilities with whatever buffer 3 holds: make it zeros
     for (int k = tid; k < AT_STAGE * AT_ROW_BYTES / 16; k += AT_THREADS)
         reinterpret_cast<uint4*>(&kv[AT_NBUF - 1][AT_STAGE * AT_ROW_BYTES])[k] = uint4{0u, 0u, 0u, 0u};
@@ -858,30 +885,6 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     };
     issue_upto(1);
 
-    // ---- this wavefront's rows: Q' = bf16(Q * scale * log2 e) into AccVGPRs, O^T to zero
-    const float c_log2 = p.scale_log2e;
-    WaveRows<MB> w;
-    static_for<0, MB>([&](auto rb_) {
-        GRAFT_CONST(rb, rb_);
-        const float c_row = (r_base + rb * 16 + l16) < p.R ? c_log2 : 0.0f;
-        static_for<0, 16>([&](auto k_) {
-            GRAFT_CONST(k, k_);
-            acc_set_bits<q_reg<MB>(rb, 0) + k>(scale_bf16_pair(qd[rb][k >> 2][k & 3], c_row));
-        });
-        w.thr[rb] = -INFINITY;
-        w.thr_min = -INFINITY;
-        w.negm[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (rb >= L_IN_ACC) w.lsum_v = floatx4{0.f, 0.f, 0.f, 0.f};
-        else
-            static_for<0, 4>([&](auto k_) {
-                GRAFT_CONST(k, k_);
-                acc_set<l_reg<MB>(rb) + k>(0.0f);
-            });
-        static_for<0, 32>([&](auto k_) {
-            GRAFT_CONST(k, k_);
-            acc_set<32 * rb + k>(0.0f);
-        });
-    });
     // Every load the compiler tracks (lengths, Q, masks, table) was consumed above, before the
     // first transfer was issued; only the transfers of stages 0 and 1 are in flight, and the
     // first advance() waits for stage 0 alone.
