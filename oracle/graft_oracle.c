@@ -15,9 +15,9 @@
  *                           contrasts itself with (Sec. 3.2, first paragraph)
  *                           and names as its online n-gram branch (Sec. 6,
  *                           limitations).  Brute-force scan of every position.
- *   oracle_build_tree_mask  "tree position IDs, ancestor mask, candidate-path
- *                           indices" rebuilt from the flattened parent list
- *                           (Sec. 3.3 "Hybrid-tree verification"; App. A,
+ *   oracle_build_tree_mask  position ids, ancestor masks and candidate path
+ *                           indices rebuilt from the flattened parent list
+ *                           (Sec. 3.3, hybrid-tree verification; App. A,
  *                           Alg. 2 last step).  Parent walk per node.
  *   oracle_tree_attn        what the tree-attention pass must produce: for
  *                           every node, ordinary causal attention of that
@@ -25,7 +25,7 @@
  *                           root-to-node path (Sec. 3.3).  Computed per path,
  *                           deliberately without any mask.
  *   oracle_accept           greedy form of the unchanged acceptance rule
- *                           (Sec. 3.3; Sec. 4 "greedy decoding"; App. B.4).
+ *                           (Sec. 3.3; greedy decoding as in Sec. 4; App. B.4).
  *
  *   oracle_matrix_retrieve  the method's own retrieval: a static template over
  *                           successor ranks filled by lookups in the transition
@@ -351,11 +351,9 @@ void oracle_accept(const int32_t* parent, const int32_t* tokens, const int32_t* 
 /* retrieval from the transition matrix                                */
 /* ------------------------------------------------------------------ */
 /*
- * The retrieval branch of the method (Sec. 3.2 "Stage-adaptive retrieval
- * templates", equation x_u = M[x_F(u), r_u]; App. A.1 "Retrieval Template
- * Details"; App. A Alg. 2 "Traverse the cached retrieval template from root
- * x_t by matrix lookup" and "Append K_ret retrieved nodes to the retained
- * draft nodes").
+ * The retrieval branch of the method (Sec. 3.2, stage-adaptive templates,
+ * equation x_u = M[x_F(u), r_u]; App. A.1; the template traversal and append
+ * steps of App. A Alg. 2).
  *
  * M is the matrix of successor ids, int32 [V][k].  The template has N nodes;
  * node u has parent tpl_parent[u] (an earlier template node, or -1 for the
@@ -405,9 +403,8 @@ void oracle_matrix_retrieve(const int32_t* M, int32_t V, int32_t k,
 /* ------------------------------------------------------------------ */
 /*
  * M[x_i] <- argtop-k(p_{i+1}) over every verified node, accepted or rejected
- * (Sec. 3.3 "Warm-up and online update", last equation; App. A equation
- * "adj_update"; App. A Alg. 1 "Update M using target logits from all verified
- * tree nodes").  The ranking of the softmax distribution is the ranking of the
+ * (Sec. 3.3, warm-up and online update, last equation; the matrix update
+ * equation and step of App. A Alg. 1).  The ranking of the softmax distribution is the ranking of the
  * logits, so no softmax is taken.
  *
  * For b = 0..B-1 and i = 0..n_nodes[b]-1 in this order: row tokens[b][i] of M
@@ -449,8 +446,8 @@ void oracle_matrix_update(const int32_t* tokens, const int32_t* n_nodes, const f
 /* cache update after acceptance                                       */
 /* ------------------------------------------------------------------ */
 /*
- * "Append accepted tokens and update target KV cache" (App. A Alg. 1; the
- * "KV/Input Update" column of the runtime table, App. D).  During verification
+ * The cache update step of App. A Alg. 1 (the KV/input update column of the
+ * runtime table, App. D).  During verification
  * tree node j has its key and value at logical position P + j.  Afterwards the
  * cache must hold the accepted path as an ordinary prefix: for k = 1 ..
  * accept_len, position P + k takes the key and value rows (all KV heads) of
@@ -510,11 +507,11 @@ void oracle_kv_compact(void* k_cache, void* v_cache, int32_t dtype, int64_t laye
 /* confidence gates and selection of the retained draft nodes          */
 /* ------------------------------------------------------------------ */
 /*
- * Dynamic-depth pruning on a finished draft tree (Sec. 3.1 "Dynamic-depth
- * pruning": cumulative path score S_{d,j} = S_{d-1,F(j)} + log q, confidence
- * c_d = exp(max_j S_{d,j}), gate g_d = 1[c_d > tau_d]; App. A Alg. 2 "Resolve
- * (K_draft, K_ret)" and "Keep the top K_draft draft nodes by cumulative path
- * score"; App. E: in the batched implementation the whole static tree is built
+ * Dynamic-depth pruning on a finished draft tree (Sec. 3.1: cumulative path
+ * score S_{d,j} = S_{d-1,F(j)} + log q, confidence
+ * c_d = exp(max_j S_{d,j}), gate g_d = 1[c_d > tau_d]; the budget resolution
+ * and top-K_draft selection steps of App. A Alg. 2; App. E: in the batched
+ * implementation the whole static tree is built
  * first and the gates are applied afterwards).
  *
  * logq[b][i] is the draft model's log-probability of node i given its parent
@@ -524,10 +521,14 @@ void oracle_kv_compact(void* k_cache, void* v_cache, int32_t dtype, int64_t laye
  * depth chk_depth[c]; the gate is taken in the log domain, max_j S_{d,j} >
  * chk_log_tau[c] (the same inequality as c_d > tau_d, without rounding an
  * exponential); a depth without nodes has confidence 0 (gate closed).  The
- * stage is the first checkpoint whose gate is closed; it keeps the chk_keep[c]
- * nodes with the largest scores (equal scores: smaller index first, so that a
- * parent comes before its child) and announces chk_ret[c] retrieval slots.  If
- * every gate is open, stage = n_chk, all nodes stay and n_ret = 0.
+ * stage is the first checkpoint whose gate is closed.  A closed gate ends the
+ * draft tree at its checkpoint: nothing deeper is expanded (Sec. 3.1; Alg. 2
+ * prunes the tree at the stage's depth before it keeps the best K_draft), so
+ * of a finished static tree only the nodes of depth <= chk_depth[c] are
+ * candidates.  The stage keeps the chk_keep[c] candidates with the largest
+ * scores (equal scores: smaller index first, so that a parent comes before its
+ * child) and announces chk_ret[c] retrieval slots.  If every gate is open,
+ * stage = n_chk, all nodes stay and n_ret = 0.
  *
  * The kept nodes are written in their old order: out_index[new] = old index,
  * out_tokens, out_parent (re-indexed), out_n_nodes; entries past the end are
@@ -563,17 +564,22 @@ void oracle_prune_select(const int32_t* parent, const int32_t* tokens, const flo
                 if (dp[i] == chk_depth[c] && S[i] > chk_log_tau[c]) open = 1;
             if (!open) st = c;
         }
+        /* candidates: the nodes the pruned tree still has (depth <= the stage's depth) */
+        const int32_t dlim = st == n_chk ? K_max : chk_depth[st];
+        int32_t n_cand = 0;
+        for (int32_t i = 0; i < n; ++i)
+            if (dp[i] <= dlim) ++n_cand;
         int32_t keep = st == n_chk ? n : chk_keep[st];
-        if (keep > n) keep = n;
+        if (keep > n_cand) keep = n_cand;
         if (keep < 1) keep = 1;
-        /* node i is kept when fewer than `keep` nodes come before it in (score, index) order */
+        /* candidate i is kept when fewer than `keep` candidates come before it in (score, index) order */
         int32_t cnt = 0;
         int ok = 1;
         for (int32_t i = 0; i < n; ++i) {
             int32_t before = 0;
             for (int32_t j = 0; j < n; ++j)
-                if (S[j] > S[i] || (S[j] == S[i] && j < i)) ++before;
-            newi[i] = before < keep ? cnt++ : -1;
+                if (dp[j] <= dlim && (S[j] > S[i] || (S[j] == S[i] && j < i))) ++before;
+            newi[i] = (dp[i] <= dlim && before < keep) ? cnt++ : -1;
             if (newi[i] >= 0 && i > 0 && newi[par[i]] < 0) ok = 0;
         }
         if (!ok) { status[b] = ST_BAD_TREE; continue; }

@@ -64,8 +64,10 @@ def test_selection_against_a_sort_and_closed_under_parents():
                     stage = c
                     break
             assert r["stage"][b] == stage
-            keep = n if stage == 3 else min(chk_keep[stage], n)
-            order = sorted(range(n), key=lambda i: (-S[i], i))[:keep]
+            # a closed gate ends the tree at its depth: deeper nodes are no candidates (Sec. 3.1; Alg. 2)
+            cand = [i for i in range(n) if stage == 3 or dp[i] <= chk_depth[stage]]
+            keep = n if stage == 3 else min(chk_keep[stage], len(cand))
+            order = sorted(cand, key=lambda i: (-S[i], i))[:keep]
             kept = sorted(order)
             assert r["n_nodes"][b] == keep and r["index"][b, :keep].tolist() == kept
             assert r["n_ret"][b] == (0 if stage == 3 else chk_ret[stage])
@@ -92,16 +94,48 @@ def test_chain_closed_form():
         closed = not (S_d > np.float32(math.log(tau)))
         assert closed == (p ** d <= tau * (1 + 1e-6))                     # the fp32 gate agrees with the real one here
         assert r["stage"].tolist() == [0 if closed else 1]
-        assert r["n_nodes"].tolist() == [3 if closed else K]
+        kept = min(3, d + 1)                                              # the pruned chain has d + 1 nodes left
+        assert r["n_nodes"].tolist() == [kept if closed else K]
         if closed:
-            assert r["index"][0, :3].tolist() == [0, 1, 2]                # the best-scoring nodes of a chain are its top
+            assert r["index"][0, :kept].tolist() == list(range(kept))     # the best-scoring nodes of a chain are its top
+
+
+def test_nodes_below_the_closed_checkpoint_are_not_candidates():
+    """Sec. 3.1: a closed gate prunes the draft tree at its checkpoint and nothing deeper is expanded (Alg. 2
+    prunes at the stage's depth, then keeps the best K_draft of what is left).  On a finished static tree
+    (App. E) a confident chain below the checkpoint must therefore not displace a shallow sibling."""
+    #        0
+    #      /   \
+    #     1     2        depth 1: scores -1/8 and -3
+    #     |
+    #     3              depth 2: -2/8
+    #     |
+    #     4              depth 3: -3/8
+    parent = np.array([[-1, 0, 0, 1, 3]], np.int32)
+    tokens = np.array([[9, 10, 20, 11, 12]], np.int32)
+    logq = np.array([[0, -0.125, -3.0, -0.125, -0.125]], np.float32)
+    # the gate at depth 1 is closed (-1/8 > 0 is false): stage 0 keeps 3 of the nodes of depth <= 1
+    r = oracle.prune_select(parent, tokens, logq, [5], [1, 2], [0.0, -9.0], [3, 4], [2, 1])
+    assert r["stage"].tolist() == [0] and r["n_nodes"].tolist() == [3] and r["n_ret"].tolist() == [2]
+    assert r["index"][0, :3].tolist() == [0, 1, 2]            # not {0, 1, 3}: node 3 scores higher than node 2 but is deeper
+    assert r["parent"][0, :3].tolist() == [-1, 0, 0] and r["tokens"][0, :3].tolist() == [9, 10, 20]
+    # fewer candidates than the stage would keep: all of them stay
+    r = oracle.prune_select(parent, tokens, logq, [5], [1, 2], [0.0, -9.0], [4, 4], [2, 1])
+    assert r["n_nodes"].tolist() == [3] and r["index"][0, :3].tolist() == [0, 1, 2]
+    # the gate at depth 2 closes instead (depth 1 open): candidates are depths 0..2, node 4 stays out
+    r = oracle.prune_select(parent, tokens, logq, [5], [1, 2], [-1.0, -0.125], [3, 4], [2, 1])
+    assert r["stage"].tolist() == [1] and r["index"][0, :4].tolist() == [0, 1, 2, 3] and r["n_nodes"].tolist() == [4]
+    # every gate open: the whole tree stays
+    r = oracle.prune_select(parent, tokens, logq, [5], [1, 2], [-1.0, -1.0], [3, 4], [2, 1])
+    assert r["stage"].tolist() == [2] and r["n_nodes"].tolist() == [5]
 
 
 def test_budget_identity_with_the_paper_s_stages():
     """Retained + retrieved = the 60-node verification budget at every stage (Sec. 3.2)."""
     rng = np.random.default_rng(1)
     K = 60
-    parent = _random_tree(rng, K, K)[None]
+    # a top-10 draft tree: ten children per expanded node, so that every stage has enough candidates
+    parent = np.array([[-1] + [(i - 1) // 10 for i in range(1, K)]], np.int32)
     logq = -rng.random((1, K)).astype(np.float32)
     for stage, (keep, ret) in enumerate(((8, 52), (24, 36), (40, 20))):
         log_tau = [-99.0] * 3
@@ -129,6 +163,7 @@ def test_gates_are_monotone_in_the_thresholds():
 def test_bad_trees_and_positive_scores():
     parent = np.array([[-1, 0, 3, 1], [-1, 0, 1, 2]], np.int32)           # node 2's parent has a larger index
     logq = np.array([[0, -1, -1, -1], [0, -5, 4, -1]], np.float32)        # positive log q lifts node 2 above its parent
-    r = oracle.prune_select(parent, np.zeros((2, 4), np.int32), logq, [4, 4], [1], [0.0], [2], [7])
+    # (checkpoint at depth 2, so that node 2 is a candidate: the best two of {0, 1, 2} are 0 and 2)
+    r = oracle.prune_select(parent, np.zeros((2, 4), np.int32), logq, [4, 4], [2], [0.0], [2], [7])
     assert r["status"].tolist() == [oracle.ST_BAD_TREE, oracle.ST_BAD_TREE]
     assert r["n_nodes"].tolist() == [0, 0] and r["stage"].tolist() == [-1, -1] and (r["index"] == -1).all()
