@@ -86,9 +86,9 @@ int32_t graft_version(void);
  *
  * This is the prompt-lookup / suffix-matching form of retrieval that the paper
  * positions its method against (Sec. 3.2 first paragraph) and names as the
- * online n-gram branch to add (Sec. 6 "Limitations and future work"); the
+ * online n-gram branch to add (Sec. 6, limitations and future work); the
  * chains it returns are what gets grafted into the released slots (Sec. 3.2
- * "merge", App. A Alg. 2 "append K_ret retrieved nodes").
+ * merge step; the append step of App. A Alg. 2).
  *
  * For sequence b let L = ctx_len[b] and q = ctx[b,0..L) followed by
  * tail[b,0..tail_len[b]) (the tokens on the tree path from below the root to
@@ -118,9 +118,10 @@ int32_t graft_retrieve(const int32_t* ctx, const int32_t* ctx_len, int32_t B, in
                        int32_t* chain_match, int32_t* n_hits, int32_t* status, void* stream);
 
 /*
- * graft_build_tree_mask - the "rebuild" step: from the flattened hybrid tree's
- * parent list to "tree position IDs, ancestor mask, and candidate-path
- * indices" (Sec. 3.3 "Hybrid-tree verification"; App. A Alg. 2, last step).
+ * graft_build_tree_mask - the rebuild step: from the flattened hybrid tree's
+ * parent list to the three things the verifier needs, position ids, ancestor
+ * masks and the node indices of every candidate path (Sec. 3.3, hybrid-tree
+ * verification; App. A Alg. 2, last step).
  *
  *     mask  [B,K_max,GRAFT_MASK_WORDS]  bit j set iff j == i or j is an ancestor of i
  *     depth [B,K_max]                   edges from the root
@@ -143,11 +144,10 @@ int32_t graft_build_tree_mask(const int32_t* parent, const int32_t* n_nodes, con
                               int32_t* status, void* stream);
 
 /*
- * graft_tree_attn - the attention inside the single parallel verification
- * pass over the hybrid tree (Sec. 3.3: the tree is sent to the target model
- * "in one parallel verification pass" with the standard ancestor mask; long
- * context runs use scaled dot-product attention, Sec. 3.3 "Long-context
- * adaptation").  One call = one layer.
+ * graft_tree_attn - the attention inside the verification pass over the hybrid
+ * tree (Sec. 3.3: the target model scores all tree nodes at once under the
+ * usual ancestor mask; the long-context runs use scaled dot-product attention,
+ * Sec. 3.3, long-context adaptation).  One call = one layer.
  *
  * For sequence b, node i < n_nodes[b], query head h (KV head g = h / (Hq/Hkv)):
  *     S   = {prefix tokens 0..P-1} U {tree slot j : bit j of mask[b,i] set},  P = prefix_len[b]
@@ -211,7 +211,7 @@ int32_t graft_attn_profile_events(void** start_events, void** stop_events, int32
 
 /*
  * graft_accept - the acceptance step under greedy decoding: the unchanged
- * speculative rule (Sec. 3.3; App. A Alg. 1 "select the accepted path";
+ * speculative rule (Sec. 3.3; the path-selection step of App. A Alg. 1;
  * App. B.4) specialised to the greedy setting of the main results (Sec. 4).
  *
  * t*[i] = the target's greedy token after node i.  Two modes:
@@ -242,10 +242,10 @@ int32_t graft_accept(const int32_t* parent, const int32_t* tokens, const int32_t
                      int32_t* status, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * graft_matrix_retrieve - the retrieval branch of the method (Sec. 3.2, "GPU-resident
- * adjacency matrix" and "Stage-adaptive retrieval templates": x_u = M[x_F(u), r_u];
- * App. A.1; App. A Alg. 2 "Traverse the cached retrieval template from root x_t by
- * matrix lookup" and "Append K_ret retrieved nodes to the retained draft nodes").
+ * graft_matrix_retrieve - the retrieval branch of the method (Sec. 3.2, the paragraphs
+ * on the GPU-resident adjacency matrix and on the stage-adaptive templates:
+ * x_u = M[x_F(u), r_u]; App. A.1; the template traversal and append steps of App. A
+ * Alg. 2).
  *
  *     M          [V,k]  int32 successor ids, -1 = empty entry (read only)
  *     tpl_parent [N]    parent template node of node u, -1 = the tree's root; < u
@@ -273,9 +273,9 @@ int32_t graft_matrix_retrieve(const int32_t* M, int32_t V, int32_t k,
 
 /*
  * graft_matrix_update - M[x_i] <- argtop-k(p_{i+1}) for every verified node, accepted
- * or rejected (Sec. 3.3 "Warm-up and online update", last equation; App. A equation
- * "adj_update"; App. A Alg. 1 "Update M using target logits from all verified tree
- * nodes").  The order of the probabilities is the order of the logits: no softmax.
+ * or rejected (Sec. 3.3, warm-up and online update, last equation; the matrix update
+ * equation and step of App. A Alg. 1).  The order of the probabilities is the order of
+ * the logits: no softmax.
  *
  *     tokens [B,K_max], n_nodes [B]   the verified tree
  *     logits [B,K_max,V] fp32         target logits per node (inputs assumed NaN-free)
@@ -298,8 +298,8 @@ int32_t graft_matrix_update(const int32_t* tokens, const int32_t* n_nodes, const
                             void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * graft_kv_compact - "Append accepted tokens and update target KV cache" (App. A
- * Alg. 1; the "KV/Input Update" column of the runtime table in App. D).  During
+ * graft_kv_compact - the cache update step of App. A Alg. 1 (the KV/input update
+ * column of the runtime table in App. D).  During
  * verification tree node j has its key and value at logical position P + j.  For
  * k = 1 .. accept_len[b], position P + k takes the key and value rows (all KV heads)
  * of position P + path[b,k]; path[b,0] = 0 is the root and stays.  Every row is read
@@ -310,7 +310,9 @@ int32_t graft_matrix_update(const int32_t* tokens, const int32_t* n_nodes, const
  *     block_table [B,max_pages], prefix_len [B]
  *     path [B,depth_cap+1], accept_len [B]   as written by graft_accept
  *     new_prefix_len [B] OUT: prefix_len + accept_len + 1 (root and accepted nodes; the
- *                        bonus token has no key yet)
+ *                        bonus token has no key yet).  Must not overlap prefix_len
+ *                        (workgroups still read the old length while it is written):
+ *                        an overlap is rejected with GRAFT_ERR_SHAPE
  * status [B]: GRAFT_STATUS_BAD_TREE if path does not start at 0, does not increase
  * strictly or reaches K_max; GRAFT_STATUS_BAD_LENGTH if prefix_len < 0, accept_len
  * outside [0,depth_cap] or a position lies beyond the block table.  Then nothing of
@@ -329,9 +331,9 @@ int32_t graft_kv_compact(void* k_cache, void* v_cache, int64_t layer_stride, int
 /*
  * graft_prune_select - dynamic-depth pruning applied to a finished draft tree (Sec. 3.1:
  * cumulative path score S_{d,j} = S_{d-1,F(j)} + log q(x_{d,j} | .), confidence
- * c_d = exp(max_j S_{d,j}), gate g_d = 1[c_d > tau_d]; App. A Alg. 2 "Resolve (K_draft,
- * K_ret)" and "Keep the top K_draft draft nodes by cumulative path score"; App. E: the
- * batched implementation builds the whole static tree first and gates afterwards).
+ * c_d = exp(max_j S_{d,j}), gate g_d = 1[c_d > tau_d]; the budget resolution and
+ * top-K_draft selection steps of App. A Alg. 2; App. E: the batched implementation
+ * builds the whole static tree first and gates afterwards).
  *
  *     parent, tokens [B,K_max], n_nodes [B]   the draft tree
  *     logq [B,K_max] fp32   log-probability of each node given its parent, <= 0 (the
@@ -342,9 +344,11 @@ int32_t graft_kv_compact(void* k_cache, void* v_cache, int64_t layer_stride, int
  * Scores are accumulated in fp32 from the root downwards.  Gate c is open when some node
  * of depth chk_depth[c] has S > chk_log_tau[c] (the inequality c_d > tau_d taken in the
  * log domain; a depth without nodes is closed).  stage [B] = first closed checkpoint, or
- * n_chk when all are open (then every node is kept and n_ret = 0).  Otherwise the
- * chk_keep[stage] nodes (at least 1, at most n_nodes) with the largest scores are kept,
- * equal scores in index order, and n_ret [B] = chk_ret[stage].
+ * n_chk when all are open (then every node is kept and n_ret = 0).  Otherwise the tree
+ * ends at the closed checkpoint (Sec. 3.1: no deeper expansion; Alg. 2 prunes at the
+ * stage's depth first): of the nodes of depth <= chk_depth[stage] the chk_keep[stage]
+ * (at least 1, at most all of them) with the largest scores are kept, equal scores in
+ * index order, and n_ret [B] = chk_ret[stage].
  *     out_index  [B,K_max]  old index of each kept node, in old order; -1 past the end
  *     out_tokens, out_parent [B,K_max]   the kept tree, parents re-indexed; -1 past the end
  *     out_n_nodes [B]

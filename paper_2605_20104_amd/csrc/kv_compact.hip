@@ -112,6 +112,9 @@ extern "C" int32_t graft_kv_compact(void* k_cache, void* v_cache, int64_t layer_
         head_stride % align != 0 || layer_stride % align != 0)
         return GRAFT_ERR_SHAPE;
     if ((reinterpret_cast<size_t>(k_cache) | reinterpret_cast<size_t>(v_cache)) & 15) return GRAFT_ERR_SHAPE;
+    // Every workgroup of a sequence reads prefix_len[b] when it starts and one of them writes
+    // new_prefix_len[b]: the two arrays must not share memory.
+    if (new_prefix_len < prefix_len + B && prefix_len < new_prefix_len + B) return GRAFT_ERR_SHAPE;
     CompactParams p{};
     p.k = k_cache; p.v = v_cache; p.block_table = block_table; p.prefix_len = prefix_len; p.path = path;
     p.accept_len = accept_len; p.new_prefix_len = new_prefix_len; p.status = status;

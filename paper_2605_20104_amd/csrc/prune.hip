@@ -24,6 +24,7 @@ __global__ __launch_bounds__(PS_THREADS) void prune_select_kernel(
     __shared__ int32_t par[PS_THREADS];
     __shared__ float S[PS_THREADS];
     __shared__ int32_t newi[PS_THREADS];
+    __shared__ int32_t dep[PS_THREADS];
     __shared__ int32_t old_of[PS_THREADS];
     __shared__ int32_t wave_cnt[PS_THREADS / 64];
     const size_t row = static_cast<size_t>(b) * K_max;
@@ -53,15 +54,23 @@ __global__ __launch_bounds__(PS_THREADS) void prune_select_kernel(
             const bool open = i < n && d == chk_depth[c] && s_i > chk_log_tau[c];
             if (__syncthreads_or(open ? 1 : 0) == 0) { st = c; break; }
         }
+        // A closed gate ends the draft tree at its checkpoint (Sec. 3.1; App. A Alg. 2 prunes at
+        // the stage's depth before it keeps the best K_draft): only nodes of depth <= dlim are
+        // candidates.  Non-candidates get a score below every real one so that the counting
+        // loop needs no second array (real scores are finite sums of finite inputs; NaN-free).
+        const int32_t dlim = st == n_chk ? K_max : chk_depth[st];
+        const bool cand = i < n && d <= dlim;
+        dep[i] = d;
+        const int32_t n_cand = __syncthreads_count(cand ? 1 : 0);
         int32_t keep = st == n_chk ? n : chk_keep[st];
-        keep = keep > n ? n : keep;
+        keep = keep > n_cand ? n_cand : keep;
         keep = keep < 1 ? 1 : keep;
         nret = st == n_chk ? 0 : chk_ret[st];
-        if (i < n) {
+        if (cand) {
             int32_t before = 0;
             for (int32_t j = 0; j < n; ++j) {
                 const float s_j = S[j];
-                before += (s_j > s_i || (s_j == s_i && j < i)) ? 1 : 0;
+                before += (dep[j] <= dlim && (s_j > s_i || (s_j == s_i && j < i))) ? 1 : 0;
             }
             kept = before < keep;
         }

@@ -195,7 +195,8 @@ def test_prune_select_validation(lib):
 
 def test_kv_compact_validation(lib):
     import paper_2605_20104_amd as g
-    ok = [P, P, 1 << 20, 4, 8 * 16 * 128, 128, 16 * 128, P, 130, P, P, P, 2, 16, 64, 8, 128, g.GRAFT_BF16, P, P, None]
+    ok = [P, P, 1 << 20, 4, 8 * 16 * 128, 128, 16 * 128, P, 130, P, P, P, 2, 16, 64, 8, 128, g.GRAFT_BF16, 0x2000, P,
+          None]
     call = _caller(lib.graft_kv_compact, ok)
     for i in (0, 1, 7, 9, 10, 11, 18, 19):
         assert call(**{"a%d" % i: None}) == g.GRAFT_ERR_NULL
@@ -208,6 +209,9 @@ def test_kv_compact_validation(lib):
     assert call(a13=g.GRAFT_MAX_NODES) == g.GRAFT_ERR_SHAPE       # depth_cap
     assert call(a14=0) == g.GRAFT_ERR_SHAPE                       # K_max
     assert call(a0=0x1008) == g.GRAFT_ERR_SHAPE                   # cache base not 16-byte aligned
+    assert call(a18=P) == g.GRAFT_ERR_SHAPE                       # new_prefix_len must not be prefix_len itself ...
+    assert call(a18=P + 4) == g.GRAFT_ERR_SHAPE                   # ... nor overlap it (B = 2 entries of 4 bytes)
+    assert call(a18=P - 4) == g.GRAFT_ERR_SHAPE
 
 
 def test_binding_has_no_fallback(monkeypatch):
