@@ -242,6 +242,30 @@ int32_t graft_accept(const int32_t* parent, const int32_t* tokens, const int32_t
                      int32_t* status, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * graft_accept_noalloc - graft_accept for callers that cannot allocate device memory or
+ * carry a workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, outputs, status flags and error codes as graft_accept
+ * without the workspace pair.  In logits mode the argmax partials (one (value, index) pair
+ * per GRAFT_ARGMAX_CHUNKS-th of every logits row) go to a 1 MiB array that is part of the
+ * library's device image (each GPU the library runs on holds its own copy until the process
+ * ends); its address is looked up on the first call per device, on the calling thread's
+ * current device.  The call allocates nothing and frees nothing.
+ *   - B * K_max <= GRAFT_NOALLOC_MAX_ROWS in logits mode, else GRAFT_ERR_WORKSPACE (nothing is
+ *     launched); target_ids mode has no such limit (it needs no scratch).
+ *   - GRAFT_ERR_HIP if the array's address cannot be obtained (graft_last_hip_error()).
+ *   - All calls on one GPU share the array: calls that may overlap in time on the same GPU
+ *     (different streams, different threads) race on it and must be ordered by the caller.
+ *     Nothing in it has to start at zero: every entry read by a call is written by that call.
+ */
+#define GRAFT_NOALLOC_MAX_ROWS 8192
+
+int32_t graft_accept_noalloc(const int32_t* parent, const int32_t* tokens, const int32_t* n_nodes,
+                             const float* logits, int32_t V, int32_t* target_ids,
+                             int32_t B, int32_t K_max, int32_t depth_cap,
+                             int32_t* accept_len, int32_t* best_node, int32_t* path, int32_t* out_tokens,
+                             int32_t* status, void* stream);
+
+/*
  * graft_matrix_retrieve - the retrieval branch of the method (Sec. 3.2, the paragraphs
  * on the GPU-resident adjacency matrix and on the stage-adaptive templates:
  * x_u = M[x_F(u), r_u]; App. A.1; the template traversal and append steps of App. A

@@ -23,6 +23,7 @@ GRAFT_MAX_NGRAM = 32
 GRAFT_PAGE_SIZE = 16
 GRAFT_MAX_SUCCESSORS = 16
 GRAFT_MAX_CHECKPOINTS = 16
+GRAFT_NOALLOC_MAX_ROWS = 8192
 GRAFT_OK, GRAFT_ERR_NULL, GRAFT_ERR_SHAPE, GRAFT_ERR_DTYPE, GRAFT_ERR_WORKSPACE, GRAFT_ERR_HIP = range(6)
 GRAFT_STATUS_BAD_LENGTH, GRAFT_STATUS_BAD_TREE, GRAFT_STATUS_PATH_OVERFLOW = 1, 2, 4
 GRAFT_F32, GRAFT_BF16 = 0, 1
@@ -44,6 +45,8 @@ _SIGNATURES = {
     "graft_accept_workspace_bytes": (_sz, [_i32] * 3),
     "graft_accept": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32,
                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "graft_accept_noalloc": (_i32, [_vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32,
+                                    _vp, _vp, _vp, _vp, _vp, _vp]),
     "graft_prune_select": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32] + [_vp] * 8),
     "graft_matrix_retrieve": (_i32, [_vp, _i32, _i32, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
     "graft_matrix_update_workspace_bytes": (_sz, [_i32] * 4),
@@ -208,6 +211,20 @@ def graft_accept(parent, tokens, n_nodes, depth_cap: int, target_ids=None, logit
         _ptr(out["accept_len"]), _ptr(out["best_node"]), _ptr(out["path"]), _ptr(out["out_tokens"]),
         _ptr(out["status"]), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream))
     _check("graft_accept", rc)
+    return out
+
+
+def graft_accept_noalloc(parent, tokens, n_nodes, depth_cap: int, out, target_ids, logits=None, stream=None):
+    """graft_accept without a workspace and without any allocation, here or in the library: every
+    output tensor is the caller's (out: accept_len, best_node, path, out_tokens, status; target_ids
+    is an input in target_ids mode and an output in logits mode)."""
+    B, K_max = parent.shape
+    V = 0 if logits is None else logits.shape[2]
+    rc = load_library().graft_accept_noalloc(
+        _ptr(parent), _ptr(tokens), _ptr(n_nodes), _ptr(logits), V, _ptr(target_ids), B, K_max, depth_cap,
+        _ptr(out["accept_len"]), _ptr(out["best_node"]), _ptr(out["path"]), _ptr(out["out_tokens"]),
+        _ptr(out["status"]), _stream(stream))
+    _check("graft_accept_noalloc", rc)
     return out
 
 

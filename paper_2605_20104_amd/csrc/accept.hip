@@ -7,6 +7,8 @@
 // sequence, one thread per node) folds the chunk partials into the target's
 // greedy token per node, checks each node's whole ancestor chain, and a
 // workgroup-wide max over (depth, -index) picks the deepest accepted node.
+#include <mutex>
+
 #include "common.h"
 
 namespace graft {
@@ -173,6 +175,67 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
     for (int32_t k = best_d + 1 + i; k < width; k += AC_THREADS) { path_b[k] = -1; out_b[k] = -1; }
 }
 
+// ---- graft_accept_noalloc: the argmax partials live in a file-scope device array ----------
+// In host code the array's name is only a stand-in for the symbol: the device address is
+// asked for once per device (hipGetSymbolAddress with that device current; every GPU holds its
+// own copy at its own address) and that pointer is what the kernels get.
+constexpr int NA_MAX_ROWS = GRAFT_NOALLOC_MAX_ROWS;   // B * K_max logits rows per call
+constexpr int NA_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[static_cast<size_t>(NA_MAX_ROWS) * GRAFT_ARGMAX_CHUNKS *
+                                                       sizeof(ArgPartial)];   // 1 MiB
+static void* g_scratch_ptr[NA_MAX_DEVICES];
+static std::mutex g_scratch_lock;
+
+// Device address of `scratch` on the current device, or nullptr (with the HIP error recorded).
+static ArgPartial* scratch_on_current_device() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= NA_MAX_DEVICES)) e = hipErrorInvalidDevice;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> hold(g_scratch_lock);
+        if (!g_scratch_ptr[dev]) {
+            void* ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e == hipSuccess && !ptr) e = hipErrorInvalidSymbol;
+            if (e == hipSuccess) g_scratch_ptr[dev] = ptr;
+        }
+        if (e == hipSuccess) return static_cast<ArgPartial*>(g_scratch_ptr[dev]);
+    }
+    (void)hipGetLastError();
+    set_last_hip_error(static_cast<int32_t>(e));
+    return nullptr;
+}
+
+static int32_t accept_impl(const int32_t* parent, const int32_t* tokens, const int32_t* n_nodes,
+                           const float* logits, int32_t V, int32_t* target_ids, int32_t B, int32_t K_max,
+                           int32_t depth_cap, int32_t* accept_len, int32_t* best_node, int32_t* path,
+                           int32_t* out_tokens, int32_t* status, ArgPartial* ws, hipStream_t s) {
+    const ArgPartial* partial = nullptr;
+    if (logits) {
+        hipLaunchKernelGGL(argmax_chunk_kernel, dim3(GRAFT_ARGMAX_CHUNKS, K_max, B), dim3(AM_THREADS), 0, s,
+                           logits, n_nodes, K_max, V, ws);
+        int32_t rc = check_launch();
+        if (rc != GRAFT_OK) return rc;
+        partial = ws;
+    }
+    hipLaunchKernelGGL(accept_walk_kernel, dim3(B), dim3(AC_THREADS), 0, s, parent, tokens, n_nodes, partial,
+                       target_ids, K_max, depth_cap, accept_len, best_node, path, out_tokens, status);
+    return check_launch();
+}
+
+static int32_t accept_args_ok(const int32_t* parent, const int32_t* tokens, const int32_t* n_nodes,
+                              const int32_t* target_ids, int32_t B, int32_t K_max, int32_t depth_cap,
+                              const int32_t* accept_len, const int32_t* best_node, const int32_t* path,
+                              const int32_t* out_tokens, const int32_t* status) {
+    if (!parent || !tokens || !n_nodes || !target_ids || !accept_len || !best_node || !path ||
+        !out_tokens || !status)
+        return GRAFT_ERR_NULL;
+    if (B < 1 || B > 65535 || K_max < 1 || K_max > GRAFT_MAX_NODES || depth_cap < 0 ||
+        depth_cap >= GRAFT_MAX_NODES)
+        return GRAFT_ERR_SHAPE;
+    return GRAFT_OK;
+}
+
 }  // namespace graft
 
 extern "C" size_t graft_accept_workspace_bytes(int32_t B, int32_t K_max, int32_t V) {
@@ -185,27 +248,34 @@ extern "C" int32_t graft_accept(const int32_t* parent, const int32_t* tokens, co
                                 int32_t K_max, int32_t depth_cap, int32_t* accept_len,
                                 int32_t* best_node, int32_t* path, int32_t* out_tokens, int32_t* status,
                                 void* workspace, size_t workspace_bytes, void* stream) {
-    if (!parent || !tokens || !n_nodes || !target_ids || !accept_len || !best_node || !path ||
-        !out_tokens || !status)
-        return GRAFT_ERR_NULL;
-    if (B < 1 || B > 65535 || K_max < 1 || K_max > GRAFT_MAX_NODES || depth_cap < 0 ||
-        depth_cap >= GRAFT_MAX_NODES)
-        return GRAFT_ERR_SHAPE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const graft::ArgPartial* partial = nullptr;
+    const int32_t rc = graft::accept_args_ok(parent, tokens, n_nodes, target_ids, B, K_max, depth_cap, accept_len,
+                                             best_node, path, out_tokens, status);
+    if (rc != GRAFT_OK) return rc;
     if (logits) {
         if (V < 1) return GRAFT_ERR_SHAPE;
         if (!workspace || workspace_bytes < graft_accept_workspace_bytes(B, K_max, V))
             return GRAFT_ERR_WORKSPACE;
-        graft::ArgPartial* ws = static_cast<graft::ArgPartial*>(workspace);
-        hipLaunchKernelGGL(graft::argmax_chunk_kernel, dim3(GRAFT_ARGMAX_CHUNKS, K_max, B),
-                           dim3(graft::AM_THREADS), 0, s, logits, n_nodes, K_max, V, ws);
-        int32_t rc = graft::check_launch();
-        if (rc != GRAFT_OK) return rc;
-        partial = ws;
     }
-    hipLaunchKernelGGL(graft::accept_walk_kernel, dim3(B), dim3(graft::AC_THREADS), 0, s, parent, tokens,
-                       n_nodes, partial, target_ids, K_max, depth_cap, accept_len, best_node, path,
-                       out_tokens, status);
-    return graft::check_launch();
+    return graft::accept_impl(parent, tokens, n_nodes, logits, V, target_ids, B, K_max, depth_cap, accept_len,
+                              best_node, path, out_tokens, status, static_cast<graft::ArgPartial*>(workspace),
+                              static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t graft_accept_noalloc(const int32_t* parent, const int32_t* tokens, const int32_t* n_nodes,
+                                        const float* logits, int32_t V, int32_t* target_ids, int32_t B,
+                                        int32_t K_max, int32_t depth_cap, int32_t* accept_len,
+                                        int32_t* best_node, int32_t* path, int32_t* out_tokens,
+                                        int32_t* status, void* stream) {
+    const int32_t rc = graft::accept_args_ok(parent, tokens, n_nodes, target_ids, B, K_max, depth_cap, accept_len,
+                                             best_node, path, out_tokens, status);
+    if (rc != GRAFT_OK) return rc;
+    graft::ArgPartial* ws = nullptr;
+    if (logits) {
+        if (V < 1) return GRAFT_ERR_SHAPE;
+        if (static_cast<int64_t>(B) * K_max > graft::NA_MAX_ROWS) return GRAFT_ERR_WORKSPACE;   // beyond the static scratch
+        ws = graft::scratch_on_current_device();
+        if (!ws) return GRAFT_ERR_HIP;
+    }
+    return graft::accept_impl(parent, tokens, n_nodes, logits, V, target_ids, B, K_max, depth_cap, accept_len,
+                              best_node, path, out_tokens, status, ws, static_cast<hipStream_t>(stream));
 }

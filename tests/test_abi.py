@@ -214,6 +214,21 @@ def test_kv_compact_validation(lib):
     assert call(a18=P - 4) == g.GRAFT_ERR_SHAPE
 
 
+def test_accept_noalloc_validation(lib):
+    import paper_2605_20104_amd as g
+    call = _caller(lib.graft_accept_noalloc, [P, P, P, None, 0, P, 2, 64, 16, P, P, P, P, P, None])
+    for i in (0, 1, 2, 5, 9, 10, 11, 12, 13):
+        assert call(**{"a%d" % i: None}) == g.GRAFT_ERR_NULL
+    assert call(a6=0) == g.GRAFT_ERR_SHAPE
+    assert call(a7=g.GRAFT_MAX_NODES + 1) == g.GRAFT_ERR_SHAPE
+    assert call(a8=g.GRAFT_MAX_NODES) == g.GRAFT_ERR_SHAPE
+    assert call(a3=P, a4=0) == g.GRAFT_ERR_SHAPE                  # logits mode needs a vocabulary
+    # more logits rows than the library's own scratch array holds: rejected before anything is launched
+    assert call(a3=P, a4=1000, a6=65, a7=128) == g.GRAFT_ERR_WORKSPACE
+    m = re.search(r"#define\s+GRAFT_NOALLOC_MAX_ROWS\s+(\d+)", open(HEADER).read())
+    assert m and int(m.group(1)) == g.GRAFT_NOALLOC_MAX_ROWS == 8192 and 65 * 128 > 8192
+
+
 def test_binding_has_no_fallback(monkeypatch):
     import paper_2605_20104_amd as g
     monkeypatch.setattr(g, "_lib", None)
