@@ -179,13 +179,16 @@ int32_t graft_build_tree_mask(const int32_t* parent, const int32_t* n_nodes, con
  *                             2^-14 of the row's largest (finer than the bf16 rounding of
  *                             the result), an absolute 2^-25 of it below that.
  * workspace                   at least graft_tree_attn_workspace_bytes(...) bytes,
- *                             256-byte aligned; contents are scratch.
+ *                             256-byte aligned; contents are scratch.  The size is 0 (and
+ *                             workspace may be NULL) for the fp32 / D = 64 path and where
+ *                             the keys of a sequence are not split over workgroups.
  *
  * Requires D in {64,128}, Hq % Hkv == 0, Hq/Hkv <= 16, page_size == GRAFT_PAGE_SIZE,
  * 1 <= K_max <= GRAFT_MAX_NODES, 1 <= max_pages <= 262144 (4 Mi tokens),
  * token_stride, head_stride and page_stride multiples of 8 elements,
  * token_stride < 2^26, all sizes positive.  The workspace size depends on the
- * device the calling thread has current (its compute-unit count picks the split).
+ * device the calling thread has current (its compute-unit count picks the split), so
+ * graft_tree_attn_workspace_bytes is a host function but not a pure one.
  */
 size_t graft_tree_attn_workspace_bytes(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int32_t D,
                                        int32_t max_pages, int32_t dtype);

@@ -38,9 +38,10 @@
 //               it a finite score and is kept while later exponents stay below
 //               2^24; beyond that the wavefront switches to an exact online
 //               softmax loop that rescales the accumulators.
-//     Partials (reference, sum, and O / sum as fp16 rows with a per-row scale)
-//     go to the workspace; a small combine kernel merges the splits and writes
-//     bf16.
+//     With one split per (sequence, KV head) the rows are normalised and written as
+//     bf16 straight from the accumulators.  Otherwise partials (reference, sum, and
+//     O / sum as fp16 rows with a per-row scale) go to the workspace; a small combine
+//     kernel merges the splits and writes bf16.
 //
 // (2) everything else (fp32 storage, or D = 64): a plain one-workgroup-per-
 //     (node, head) kernel in fp32.  It serves the tiny fp32 configuration and as
@@ -686,6 +687,36 @@ __device__ __forceinline__ void pv_only(const unsigned char* __restrict__ Vs, Wa
     for (int rb = 0; rb < MB; ++rb) GRAFT_KEEP(pb[rb]);
 }
 
+// One split only: O / l as bf16, straight from the accumulators.  Lane (l16, lg) holds row l16 of
+// each row block, dims 16 db + 4 lg .. +3 of dim block db.  Rows of absent nodes are zeros.
+template <int MB>
+__device__ __forceinline__ void store_rows(const AttnParams& p, const WaveRows<MB>& w, int b, int g, int r_base,
+                                           int n, int lane) {
+    const int l16 = lane & 15, lg = lane >> 4;
+    static_for<0, MB>([&](auto rb_) {
+        GRAFT_CONST(rb, rb_);
+        const int r = r_base + rb * 16 + l16;
+        float l;
+        if constexpr (rb >= L_IN_ACC) l = w.lsum_v[0];
+        else l = acc_get<l_reg<MB>(rb)>();
+        const int i = (r * p.g_magic) >> 16, hl = r - i * p.G;                  // i = r / G
+        const bool keep = i < n && l > 0.f;
+        const float inv_l = keep ? 1.0f / l : 0.f;
+        unsigned short* outp = static_cast<unsigned short*>(p.out) +
+            ((static_cast<int64_t>(b) * p.K_max + i) * p.Hq + g * p.G + hl) * AT_D + 4 * lg;
+        static_for<0, 8>([&](auto db_) {
+            GRAFT_CONST(db, db_);
+            float o[4];
+            static_for<0, 4>([&](auto k_) {
+                GRAFT_CONST(k, k_);
+                const float v = acc_get<o_reg(rb, db) + k>();
+                o[k] = keep ? v * inv_l : 0.f;
+            });
+            if (r < p.R) *reinterpret_cast<uint2*>(outp + 16 * db) = uint2{pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+        });
+    });
+}
+
 // Rounds q * f to bf16 for two packed bf16 values.
 __device__ __forceinline__ unsigned scale_bf16_pair(unsigned q2, float f) {
     return pack_bf16(__uint_as_float(q2 << 16) * f, __uint_as_float(q2 & 0xffff0000u) * f);
@@ -1006,6 +1037,16 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     }
     GRAFT_MFMA_SETTLE();
 
+    if (p.n_splits == 1) {
+        // ---- one split: this workgroup holds the whole result of its rows
+        // (the lane index goes through an empty asm: otherwise the compiler keeps the row
+        //  addressing it computed for the Q loads in registers across the whole loop, registers
+        //  that the loop does not have)
+        int lane_out = lane;
+        asm volatile("" : "+v"(lane_out));
+        store_rows<MB>(p, w, b, g, r_base, sr.n, lane_out);
+        return;
+    }
     // ---- partial results.  Per row and split: the reference max m (log2 units), the row sum l
     //      and O / l, which is a convex combination of V rows, stored as fp16 after an exact
     //      scaling by a power of two 2^-e that brings the row's largest magnitude into
@@ -1339,9 +1380,11 @@ static AttnPlan make_plan(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
         }
     }
     pl.r_pad = pl.n_row_tiles * pl.mb * rows_per_mb;
-    const size_t rows = static_cast<size_t>(B) * Hkv * pl.n_splits * pl.r_pad;
-    pl.ws_o_bytes = rows * AT_D * sizeof(unsigned short);       // fp16 rows
-    pl.ws_bytes = pl.ws_o_bytes + rows * 4 * sizeof(float);
+    if (pl.n_splits > 1) {                                       // one split needs no workspace and no merge
+        const size_t rows = static_cast<size_t>(B) * Hkv * pl.n_splits * pl.r_pad;
+        pl.ws_o_bytes = rows * AT_D * sizeof(unsigned short);   // fp16 rows
+        pl.ws_bytes = pl.ws_o_bytes + rows * 4 * sizeof(float);
+    }
     return pl;
 }
 
@@ -1440,7 +1483,7 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
         default: launch_main(tree_attn_mfma_kernel<5>, grid, dim3(AT_THREADS), s, p); break;
     }
     int32_t rc = check_launch();
-    if (rc != GRAFT_OK) return rc;
+    if (rc != GRAFT_OK || pl.n_splits == 1) return rc;
     // wpt wavefronts per tile pair (cb_u splits each); as many tile pairs per workgroup as
     // make the workgroups one round (or, capped, a few whole rounds) over the compute units
     const int64_t n_tiles = static_cast<int64_t>(B) * Hkv * (pl.r_pad / 16) * (AT_D / 32);

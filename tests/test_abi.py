@@ -118,6 +118,7 @@ def test_tree_attn_validation_and_workspace(lib):
     assert ws(1, 40, 32, 8, 96, 130, g.GRAFT_BF16) == 0   # unsupported shape -> 0
     # more sequences never need less workspace
     assert ws(4, 96, 32, 8, 128, 4102, g.GRAFT_BF16) >= ws(1, 96, 32, 8, 128, 4102, g.GRAFT_BF16)
+    assert ws(64, 16, 8, 8, 128, 40, g.GRAFT_BF16) == 0   # enough (sequence, head) units to fill the chip: one split
 
 
 def test_accept_validation(lib):

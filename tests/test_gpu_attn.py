@@ -1,7 +1,13 @@
 """GPU parity: graft_tree_attn vs the CPU oracle (MI355X only).
 
 Tolerances: bf16 storage with fp32 accumulation must be within 2e-2 max-abs of the
-fp64 oracle (outputs compared in fp32); the fp32 path within 1e-4.
+fp64 oracle (outputs compared in fp32); the fp32 path within 1e-4.  The 2e-2 holds for inputs
+like the workloads' (N(0,1) operands: scaled scores of unit size).  The bf16 path rounds the
+pre-scaled query q * scale * log2(e) to bf16 once, a relative 2^-9 per element on top of the
+bf16 storage of q; the noise this puts on a score, and with it on a softmax weight, grows in
+proportion to the size of the scores.  A test that multiplies the scores by s on purpose
+therefore allows s times the tolerance for the largest error (and checks the rms error
+against the plain tolerance): score_scale_tolerance().
 """
 import dataclasses
 import math
@@ -18,6 +24,16 @@ from gpu_util import dev, host, run_attn
 pytestmark = pytest.mark.gpu
 TOL_BF16 = 2e-2
 TOL_F32 = 1e-4
+
+
+def score_scale_tolerance(got, ref, s_rms, what):
+    """Largest error within TOL_BF16 * max(1, s_rms), s_rms = the rms size of the scaled scores (1 for
+    the workloads' inputs); rms error within TOL_BF16 / 4.  Prints what was measured."""
+    err = np.abs(got.astype(np.float64) - np.asarray(ref, np.float64))
+    rms = float(np.sqrt((err ** 2).mean()))
+    print("%s: max abs err %.3e, rms err %.3e, largest |ref| %.2f, score rms %.2f"
+          % (what, err.max(), rms, np.abs(ref).max(), s_rms))
+    assert err.max() <= TOL_BF16 * max(1.0, s_rms) and rms <= TOL_BF16 / 4
 
 
 def gpu_mask(parent, n_nodes, prefix):
@@ -80,6 +96,7 @@ MFMA_CASES = [
     (1, 20, 16, 16, 31),      # group size 1
     (1, 128, 32, 2, 100),     # R = 2048: the largest row count, seven row tiles
     (16, 8, 16, 8, 95),       # many sequences, few rows: one workgroup per (sequence, head)
+    (1, 64, 40, 8, 20000),    # R = 320 with five row blocks per wavefront and more than 16 splits, every row
 ]
 
 
@@ -176,7 +193,8 @@ def test_large_scores_stay_finite():
     ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
                            att["block_table"], [w.P], [w.K], parent, w.Hq, w.Hkv, w.D, 16, att["scale"])
     assert np.isfinite(got).all()
-    assert np.abs(got - ref.astype(np.float32)).max() <= 4e-2      # bf16 rounding of O(4) outputs
+    s_rms = float(np.sqrt(w.D) * att["scale"] * 6.0)                # q and k are N(0,1), q times 6
+    score_scale_tolerance(got, ref, s_rms, "peaked softmax")
 
 
 def test_scores_that_outgrow_the_reference():
@@ -206,7 +224,9 @@ def test_scores_that_outgrow_the_reference():
     ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
                            att["block_table"], prefix, n_nodes, parent, w.Hq, w.Hkv, w.D, 16, att["scale"])
     assert np.isfinite(got).all()
-    assert np.abs(got - ref.astype(np.float32)).max() <= 4e-2       # outputs are single V rows of size O(4)
+    err = np.abs(got - ref.astype(np.float32)).max()
+    print("scores outgrow the reference: max abs err %.3e" % err)
+    assert err <= TOL_BF16
 
 
 @pytest.mark.parametrize("log2_scale", [-100, -20, 40, 100])
@@ -265,7 +285,9 @@ def test_scores_that_outgrow_the_reference_in_long_splits():
     ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
                            att["block_table"], prefix, n_nodes, parent, w.Hq, w.Hkv, w.D, 16, att["scale"])
     assert np.isfinite(got).all()
-    assert np.abs(got - ref.astype(np.float32)).max() <= 4e-2       # outputs are single V rows of size O(4)
+    err = np.abs(got - ref.astype(np.float32)).max()
+    print("scores outgrow the reference: max abs err %.3e" % err)
+    assert err <= TOL_BF16
 
 
 def test_c2_full_size_all_rows():
@@ -280,25 +302,64 @@ def test_c2_full_size_all_rows():
     assert np.abs(got - ref.astype(np.float32)).max() <= TOL_BF16
 
 
-@pytest.mark.parametrize("name,n_rows", [("c3", 96), ("c4", 96), ("c5", 48)])
-def test_full_size_sampled_rows(name, n_rows):
-    """Full benchmark sizes in the benchmark's launch configuration; the oracle computes a
-    seeded sample of (sequence, node, head) rows, always including deep nodes."""
+@pytest.mark.parametrize("name", ["c3", "c4", "c5"])
+def test_full_size_all_rows(name):
+    """Full benchmark sizes in the benchmark's launch configuration, every (sequence, node, head) row
+    against the oracle."""
     w = inputs.get_workload(name)
     s = inputs.make_step_inputs(w)
     att = inputs.make_attention_inputs(w, kv_buffers=1)
     mask = gpu_mask(s["parent"], s["n_nodes"], s["prefix_len"])
     got = run_attn(att, "bf16", s["prefix_len"], s["n_nodes"], mask, w.Hkv)
-    rng = np.random.default_rng(w.index)
-    rows = np.stack([rng.integers(0, w.B, n_rows), rng.integers(0, w.K, n_rows),
-                     rng.integers(0, w.Hq, n_rows)], axis=1).astype(np.int32)
-    rows[0] = (0, 0, 0)
-    rows[1] = (w.B - 1, w.K - 1, w.Hq - 1)
     ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
                            att["block_table"], s["prefix_len"], s["n_nodes"], s["parent"], w.Hq, w.Hkv, w.D,
-                           16, att["scale"], rows=rows)
-    sel = np.stack([got[b, i, h] for b, i, h in rows])
+                           16, att["scale"])
     assert np.isfinite(got).all()
-    assert np.abs(sel - ref.astype(np.float32)).max() <= TOL_BF16
-    # property that holds at any size: every output is a convex combination of V rows
-    assert np.abs(got).max() <= 6.5
+    err = np.abs(got - ref.astype(np.float32)).max()
+    print("%s all %d rows: max abs err %.3e" % (name, w.B * w.K * w.Hq, err))
+    assert err <= TOL_BF16
+
+
+def _plan_splits(B, K, Hq, Hkv, max_pages):
+    """Number of KV splits the library plans: read off the workspace size (272 bytes per partial row;
+    one split needs no workspace)."""
+    R = K * (Hq // Hkv)
+    assert R <= 320
+    r_pad = -(-R // 64) * 64
+    ws = graft.graft_tree_attn_workspace_bytes(B, K, Hq, Hkv, 128, max_pages, graft.GRAFT_BF16)
+    if ws == 0:
+        return 1
+    assert ws % (B * Hkv * r_pad * 272) == 0
+    return ws // (B * Hkv * r_pad * 272)
+
+
+def test_many_splits_agree_with_a_single_split():
+    """The split-KV merge against a run that needs none: the same sequence alone (a batch of one is cut
+    into many splits) and replicated 64 times (enough (sequence, head) units to fill the chip, so the
+    plan takes one split).  Outputs may differ by the rounding of the partial results only (fp16 rows
+    scaled to each split's own largest entry, which is larger than the merged row's) and by a final
+    bf16 rounding that flips: within one bf16 unit in the last place of the row's largest entry."""
+    w1 = shape_workload(1, 24, 16, 4, 128, 6000)
+    att = inputs.make_attention_inputs(w1, seed=31)
+    rng = np.random.default_rng(31)
+    parent = np.stack([inputs.random_recursive_tree(rng, w1.K, 8)])
+    n1, p1 = np.array([w1.K], np.int32), np.array([w1.P], np.int32)
+    pages = att["block_table"].shape[1]
+    assert _plan_splits(1, w1.K, w1.Hq, w1.Hkv, pages) >= 16
+    one = run_attn(att, "bf16", p1, n1, gpu_mask(parent, n1, p1), w1.Hkv)
+    B = 64
+    assert _plan_splits(B, w1.K, w1.Hq, w1.Hkv, pages) == 1
+    rep = dict(att, q=[np.repeat(att["q"][0], B, axis=0)], block_table=np.repeat(att["block_table"], B, axis=0))
+    nB, pB = np.full(B, w1.K, np.int32), np.full(B, w1.P, np.int32)
+    many = run_attn(rep, "bf16", pB, nB, gpu_mask(np.repeat(parent, B, axis=0), nB, pB), w1.Hkv)
+    assert (many == many[0:1]).all()                           # every replica computes the same thing
+    diff = np.abs(one[0].astype(np.float64) - many[0])
+    ulp = np.exp2(np.floor(np.log2(np.maximum(np.abs(many[0]), 1e-30))) - 7)
+    row_max = np.abs(many[0]).max(axis=-1, keepdims=True)
+    print("split vs single: %d of %d entries differ, max %.3e" % (int((diff > 0).sum()), diff.size, diff.max()))
+    row_ulp = np.exp2(np.floor(np.log2(row_max)) - 7)
+    print("largest difference in units of the row's bf16 ulp: %.3f" % (diff / row_ulp).max())
+    assert (diff <= np.maximum(ulp, row_ulp)).all()
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
+                           att["block_table"], p1, n1, parent, w1.Hq, w1.Hkv, w1.D, 16, att["scale"])
+    assert np.abs(one - ref.astype(np.float32)).max() <= TOL_BF16 and np.abs(many[:1] - ref.astype(np.float32)).max() <= TOL_BF16

@@ -71,5 +71,6 @@ def test_prune_select_deep_chain_and_star():
 def test_prune_select_error_paths():
     parent = np.array([[-1, 0, 3, 1], [-1, 0, 1, 2], [-1, 0, 0, 0], [0, 0, 0, 0]], np.int32)
     logq = np.array([[0, -1, -1, -1], [0, -5, 4, -1], [0, -1, -1, -1], [0, -1, -1, -1]], np.float32)
-    ref = _both(parent, np.zeros((4, 4), np.int32), logq, [4, 4, 5, 4], [1], [0.0], [2], [7])
+    # (checkpoint at depth 2, so that the node whose positive log q lifts it above its parent is a candidate)
+    ref = _both(parent, np.zeros((4, 4), np.int32), logq, [4, 4, 5, 4], [2], [0.0], [2], [7])
     assert ref["status"].tolist() == [graft.GRAFT_STATUS_BAD_TREE] * 4
