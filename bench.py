@@ -83,6 +83,8 @@ def main():
                     help="also time the steps around verification (matrix retrieval, matrix refresh from the "
                          "logits, cache update after acceptance) and report them in extra keys; the timed step "
                          "and the headline metric stay the same")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default run only: do not time c5 and c2 after the c3 steps")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run five plain 1 GiB -> 1 GiB elementwise copies and exit: the reference that the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by")
@@ -111,11 +113,51 @@ def main():
         print(json.dumps({"copy_calibration": True, "bytes_read_per_launch": n * 4,
                           "bytes_written_per_launch": n * 4, "launches": 5}))
         return
-    hip = Hip()
-
-    w = inputs.get_workload(args.workload)
-    steps = args.steps if args.steps is not None else {"c1": 200, "c2": 100, "c3": 100, "c4": 20, "c5": 30}[w.name]
+    steps = args.steps if args.steps is not None else {"c1": 200, "c2": 100, "c3": 100, "c4": 20, "c5": 30}[args.workload]
     warmup = args.warmup if args.warmup is not None else 10
+    result = run_workload(args, args.workload, steps, warmup, light=False)
+    if args.workload == "c3" and not args.no_other_workloads:
+        # the largest and the short-context workload ride along with few steps (kernel time, roofline
+        # fractions, step time), and a plain copy kernel gives the bandwidth this box really reaches
+        result["practical_hbm_GBps"] = round(copy_bandwidth_GBps(), 1)
+        result["other_workloads"] = {}
+        for name, st in (("c5", 12), ("c2", 30)):
+            r = run_workload(args, name, st, 3, light=True)
+            result["other_workloads"][name] = {
+                "workload": r["config"]["workload"], "steps": st, "us_per_step": r["us_per_step"],
+                "kernel_avg_us": r["roofline"]["kernel_avg_us"], "frac": r["roofline"]["frac"],
+                "achieved_GBps": r["roofline"]["achieved"], "mfma_frac": r["roofline"]["mfma_frac"],
+                "attn_call_us": r["per_call_us"]["tree_attn_layer"],
+            }
+    print(json.dumps(result))
+
+
+def copy_bandwidth_GBps():
+    """Read + write rate of a plain elementwise copy of 1 GiB (torch's kernel), best of 5."""
+    import torch
+    n = (1 << 30) // 4
+    src = torch.ones(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    best = 0.0
+    for _ in range(6):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        torch.mul(src, 1.0, out=dst)
+        b.record()
+        torch.cuda.synchronize()
+        best = max(best, 2.0 * n * 4 / (a.elapsed_time(b) * 1e-3) / 1e9)
+    del src, dst
+    torch.cuda.empty_cache()
+    return best
+
+
+def run_workload(args, name, steps, warmup, light):
+    """Times `steps` steps of workload `name`; light = no per-call extras, no CPU baseline."""
+    import torch
+    import inputs
+    import paper_2605_20104_amd as graft
+    hip = Hip()
+    w = inputs.get_workload(name)
     att_bytes, att_flops = attention_bytes_and_flops(w)
 
     # ---- inputs -> HBM
@@ -252,7 +294,7 @@ def main():
 
     # ---- optional: the steps around verification, each timed on its own (medians)
     extended = None
-    if args.extended:
+    if args.extended and not light:
         from inputs import templates
         tp, tr, _, sizes = templates.retrieval_envelope()
         kk = 8
@@ -313,7 +355,7 @@ def main():
 
     # ---- optional: the same step replayed from a captured HIP graph (launch overhead removed)
     graph_us = None
-    if args.graph:
+    if args.graph and not light:
         side = torch.cuda.Stream()
         with torch.cuda.stream(side):
             step()                                   # warm-up on the capture stream
@@ -384,9 +426,11 @@ def main():
         },
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not light:
         result["cpu_baseline"] = cpu_baseline(w, s, att, att_bytes, args.cpu_seconds)
-    print(json.dumps(result))
+    del kc, vc, q
+    torch.cuda.empty_cache()
+    return result
 
 
 def cpu_baseline(w, s, att, att_bytes, budget_s):

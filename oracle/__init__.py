@@ -23,20 +23,43 @@ MASK_WORDS = 2
 _lib = None
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (-O2, OpenMP, no fast-math)."""
-    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        tmp = _SO + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC",
+_SO_SAN = os.path.join(_HERE, "libgraft_oracle_san.so")
+SANITIZE_ENV = "GRAFT_ORACLE_SANITIZE"       # set to 1: the tests run against the sanitized build
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math).
+
+    sanitize=True builds a second library with AddressSanitizer and UndefinedBehaviorSanitizer
+    (every report is fatal).  A process can only load it when the AddressSanitizer runtime was
+    loaded first (see sanitizer_env()).
+    """
+    so = _SO_SAN if sanitize else _SO
+    if force or not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(_SRC):
+        tmp = so + ".tmp%d" % os.getpid()
+        flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                 "-fno-omit-frame-pointer"] if sanitize else ["-O2"]
+        subprocess.check_call(["gcc", *flags, "-std=c11", "-fopenmp", "-shared", "-fPIC",
                                "-Wall", "-Wextra", _SRC, "-o", tmp, "-lm"])
-        os.replace(tmp, _SO)
-    return _SO
+        os.replace(tmp, so)
+    return so
+
+
+def sanitizer_env(env=None) -> dict:
+    """Environment for a child process that is to load the sanitized build: the switch that makes
+    this module pick it, and the AddressSanitizer runtime in front of whatever is preloaded already."""
+    env = dict(os.environ if env is None else env)
+    asan = subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
+    env[SANITIZE_ENV] = "1"
+    env["LD_PRELOAD"] = asan + (":" + env["LD_PRELOAD"] if env.get("LD_PRELOAD") else "")
+    env["ASAN_OPTIONS"] = "detect_leaks=0:abort_on_error=1"      # the interpreter's own leaks are not the subject
+    return env
 
 
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        _lib = ctypes.CDLL(build(sanitize=os.environ.get(SANITIZE_ENV) == "1"))
     return _lib
 
 

@@ -45,7 +45,7 @@ def _compile(src: str, extra):
 
 
 def _reg_span(tok: str):
-    """'v12' -> ('v', 12, 12); 'a[4:7]' -> ('a', 4, 7); numbers may be hexadecimal; else None."""
+    """'v12' -> ('v', 12, 12); 'a[4:7]' -> ('a', 4, 7); 'a[0xf0]' -> ('a', 240, 240); else None."""
     m = re.fullmatch(r"([va])(\d+|0x[0-9a-f]+)", tok)
     if m:
         n = int(m.group(2), 0)
@@ -53,7 +53,16 @@ def _reg_span(tok: str):
     m = re.fullmatch(r"([va])\[(\d+|0x[0-9a-f]+):(\d+|0x[0-9a-f]+)\]", tok)
     if m:
         return m.group(1), int(m.group(2), 0), int(m.group(3), 0)
+    m = re.fullmatch(r"([va])\[(\d+|0x[0-9a-f]+)\]", tok)
+    if m:
+        n = int(m.group(2), 0)
+        return m.group(1), n, n
     return None
+
+
+# Wait states between an MFMA and the first other instruction that may read its result: the
+# passes of the widest MFMA used here (8) plus 3, as for the compiler's own MFMAs, plus one.
+MFMA_RESULT_WAIT = 12
 
 
 def check_attention_asm(asm_text: str):
@@ -66,17 +75,30 @@ def check_attention_asm(asm_text: str):
         and the compiler must not touch them);
       * no MFMA has a vector ALU instruction writing one of its VGPR sources within the two
         preceding wait states (an s_nop k counts k + 1): the hardware needs them and the
-        compiler does not know that the asm statement is an MFMA.
+        compiler does not know that the asm statement is an MFMA.  The same holds for a
+        v_accvgpr_write of an AccVGPR source;
+      * no instruction other than an MFMA reads a register that an MFMA wrote within the
+        MFMA_RESULT_WAIT preceding wait states, in program order across labels (the result of a
+        16x16x32 MFMA is written at the end of its passes, and nothing interlocks a vector ALU,
+        LDS or memory instruction, or a v_accvgpr_read, that comes earlier).
     """
     problems = []
     lines = asm_text.split("\n")
     kernel, mb, in_asm, desc = None, 0, False, ""
     history = []          # (wait states, destination span or None) of the preceding instructions
+    results = []          # [wait states since, span] of MFMA results still inside MFMA_RESULT_WAIT
+
+    def age(states):
+        for r in results:
+            r[0] += states
+        while results and results[0][0] >= MFMA_RESULT_WAIT:
+            del results[0]
+
     for ln, raw in enumerate(lines, 1):
         text = raw.split(";")[0].strip() if not raw.lstrip().startswith(";") else ""
         m = re.match(r"^(_ZN5graft21tree_attn_mfma_kernelILi(\d+)E\w*):", raw)
         if m:
-            kernel, mb, history = m.group(1), int(m.group(2)), [(1, ("v", 0, 1 << 20))]
+            kernel, mb, history, results = m.group(1), int(m.group(2)), [(1, ("v", 0, 1 << 20))], []
             continue
         if kernel and raw.startswith(".Lfunc_end"):
             kernel = None
@@ -114,27 +136,44 @@ def check_attention_asm(asm_text: str):
                     problems.append("line %d (%s): compiler-generated use of a hand-managed AccVGPR: %s"
                                     % (ln, kernel, text))
         if op.startswith("v_mfma"):
-            srcs = [sp for sp in map(_reg_span, args[1:]) if sp and sp[0] == "v"]
+            srcs = [sp for sp in map(_reg_span, args[1:]) if sp]
             states = 0
             for w, dst in reversed(history):
                 if states >= 2:
                     break
-                if dst is not None and any(dst[1] <= s_[2] and s_[1] <= dst[2] for s_ in srcs):
+                if dst is not None and any(dst[0] == s_[0] and dst[1] <= s_[2] and s_[1] <= dst[2] for s_ in srcs):
                     problems.append("line %d (%s): vector ALU write of an MFMA source %d wait state(s) before: %s"
                                     % (ln, kernel, states, text))
                     break
                 states += w
             history.append((1, None))
+            age(1)
+            d = _reg_span(args[0]) if args else None
+            if d:
+                results.append([0, d])
             continue
         if op == "s_nop":
             history.append((int(args[0], 0) + 1, None))
+            age(int(args[0], 0) + 1)
             continue
+        # any other instruction: it must not read what an MFMA has just written (stores and LDS
+        # writes have no destination: all their operands are read)
+        reads = args if op.startswith(("global_store", "buffer_store", "flat_store", "ds_write", "ds_store",
+                                       "global_atomic", "v_cmp")) else args[1:]
+        for a in reads:
+            sp = _reg_span(a)
+            hit = sp and next((r for r in results if r[1][0] == sp[0] and r[1][1] <= sp[2] and sp[1] <= r[1][2]), None)
+            if hit:
+                problems.append("line %d (%s): read of an MFMA result %d wait state(s) after the MFMA: %s"
+                                % (ln, kernel, hit[0], text))
+                break
         dst = None
         if op.startswith("v_") and not op.startswith(("v_cmp", "v_readlane", "v_readfirstlane")) and args:
             sp = _reg_span(args[0])
-            if sp and sp[0] == "v":
+            if sp and (sp[0] == "v" or op.startswith("v_accvgpr_write")):
                 dst = sp
         history.append((1, dst))
+        age(1)
         if len(history) > 8:
             del history[0]
     return problems

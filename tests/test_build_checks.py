@@ -71,6 +71,41 @@ def test_compiler_use_of_a_hand_managed_accvgpr():
     assert b.check_attention_asm(_asm(FILL + "\n" + inside)) == []
 
 
+NOPS = "\ts_nop 7\n\ts_nop 3"          # 8 + 4 = 12 wait states
+
+
+@pytest.mark.parametrize("reader", ["v_exp_f32_e32 v1, v41", "v_max3_f32 v2, v3, v40, v43", "ds_write_b32 v5, v42",
+                                    "global_store_dwordx4 v[6:7], v[40:43], off", "v_cmp_gt_f32_e32 vcc, v40, v1",
+                                    "v_accvgpr_write_b32 a200, v43"])
+def test_read_of_an_mfma_result_in_vgprs_too_early(reader):
+    bad = b.check_attention_asm(_asm(FILL + "\n" + MFMA_C + "\n\t" + reader))
+    assert len(bad) == 1 and "MFMA result" in bad[0]
+    # eleven wait states are not enough, twelve are; a label in between does not reset the count
+    assert b.check_attention_asm(_asm(FILL + "\n" + MFMA_C + "\n\ts_nop 7\n\ts_nop 2\n\t" + reader))
+    assert b.check_attention_asm(_asm(FILL + "\n" + MFMA_C + "\n" + NOPS + "\n\t" + reader)) == []
+    assert b.check_attention_asm(_asm(FILL + "\n" + MFMA_C + "\n\ts_nop 3\n.LBB0_7:\n\t" + reader))
+    # registers next to the result are not the result
+    other = reader.replace("v40", "v39").replace("v41", "v44").replace("v42", "v44").replace("v43", "v44") \
+                  .replace("v[40:43]", "v[44:47]")
+    assert b.check_attention_asm(_asm(FILL + "\n" + MFMA_C + "\n\t" + other)) == []
+
+
+def test_read_of_an_accumulator_too_early():
+    rd = "\t;;#ASMSTART\n\tv_accvgpr_read_b32 v1, a[2]\n\t;;#ASMEND"
+    bad = b.check_attention_asm(_asm(FILL + "\n" + MFMA + "\n" + rd))
+    assert len(bad) == 1 and "MFMA result" in bad[0]
+    assert b.check_attention_asm(_asm(FILL + "\n" + MFMA + "\n" + NOPS + "\n" + rd)) == []
+    # another MFMA accumulating into the same registers is not such a reader
+    assert b.check_attention_asm(_asm(FILL + "\n" + MFMA + "\n" + MFMA)) == []
+
+
+def test_accvgpr_write_of_a_source_right_before_the_mfma():
+    wr = "\t;;#ASMSTART\n\tv_accvgpr_write_b32 a[97], v1\n\t;;#ASMEND"
+    bad = b.check_attention_asm(_asm(FILL + "\n" + wr + "\n" + MFMA_C))
+    assert len(bad) == 1 and "MFMA source" in bad[0]
+    assert b.check_attention_asm(_asm(FILL + "\n" + wr + "\n\ts_nop 1\n" + MFMA_C)) == []
+
+
 def test_scratch_memory():
     bad = b.check_attention_asm(_asm(FILL, scratch=128))
     assert len(bad) == 1 and "scratch" in bad[0]
