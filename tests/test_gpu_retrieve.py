@@ -54,6 +54,20 @@ def test_periodic_long_buffer_and_limits():
     assert gpu["n_hits"][0] == 69999
 
 
+def test_long_tail_and_query_in_every_place():
+    """The query can lie in the tail alone, across the end of the context and the tail, or in the context
+    beyond the first chunks; tails longer than a workgroup has threads are read from memory."""
+    rng = np.random.default_rng(11)
+    B, L_max, tail_max = 4, 40000, 1100
+    ctx = rng.integers(0, 6, size=(B, L_max)).astype(np.int32)
+    tail = rng.integers(0, 6, size=(B, tail_max)).astype(np.int32)
+    ctx_len = np.array([40000, 33000, 16385, 5], np.int32)
+    tail_len = np.array([1100, 3, 1060, 0], np.int32)
+    gpu, ref = both(ctx, ctx_len, 2, 32, 8, 7, tail, tail_len)
+    assert_same(gpu, ref, KEYS)
+    assert gpu["status"].tolist() == [0, 0, 0, 0] and gpu["n_hits"][0] > 0
+
+
 def test_no_hits_and_bad_lengths():
     ctx = np.arange(500, dtype=np.int32).reshape(1, 500).repeat(3, 0)
     gpu, ref = both(ctx, [500, 501, -1], 1, 4, 2, 4)
