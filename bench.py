@@ -249,7 +249,7 @@ def run_workload(args, name, steps, warmup, light):
 
     # ---- timed region: exactly `steps` steps; the library attaches an event pair to the main
     #      attention kernel of its first n_ev attention calls
-    n_ev = min(steps * w.layers, 256)      # attaching events costs host time per launch: bound it
+    n_ev = min(steps * w.layers, 64 if light else 256)      # attaching events costs host time per launch: bound it
     ev_a = (ctypes.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)])
     ev_b = (ctypes.c_void_p * n_ev)(*[hip.event() for _ in range(n_ev)])
     lib = graft.load_library()
