@@ -326,11 +326,14 @@ __device__ __forceinline__ bf16x8 load_k_operand(const unsigned char* Ks, int g,
 // (half c = tokens 16c .. 16c + 15 of the sub-tile: one transpose read, elements 4c .. 4c + 3)
 template <int C>
 __device__ __forceinline__ void load_v_half(bf16x8& va, const unsigned char* Vs, int db, int l16, int lg) {
-    const int row = 16 * C + 4 * lg + (l16 >> 2);
-    const int seg = db ^ (row & 7);
-    const unsigned char* ptr = Vs + row * AT_ROW_BYTES + seg * 32 + 8 * (l16 & 3);
+    // row 16C + 4lg + (l16 >> 2), 32-byte segment db ^ (row & 7): the segment is bits 5-7 of the
+    // address, row & 7 does not depend on C, and sub-tiles start at multiples of 256 bytes, so
+    // the address is the lane's base (which carries row & 7 in those bits) XOR db << 5, plus a
+    // constant for C that fits the read's offset field: one vector instruction per dim block.
+    const int row0 = 4 * lg + (l16 >> 2);
+    const unsigned base = lds_address(Vs) + row0 * AT_ROW_BYTES + ((row0 & 7) << 5) + 8 * (l16 & 3);
     const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (short4_t __attribute__((address_space(3)))*)(ptr));
+        (short4_t __attribute__((address_space(3)))*)(static_cast<size_t>((base ^ (db << 5)) + C * 16 * AT_ROW_BYTES)));
     const bf16x4 r4 = __builtin_bit_cast(bf16x4, r);
     va[4 * C + 0] = r4[0];
     va[4 * C + 1] = r4[1];
