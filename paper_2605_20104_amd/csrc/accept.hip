@@ -99,6 +99,7 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
     __shared__ int32_t tstar[AC_THREADS];
     __shared__ u64 red[AC_THREADS / 64];
     __shared__ int32_t best_d;
+    __shared__ int32_t or_bad[2], or_over[2];
 
     const int32_t n = n_nodes[b];
     const bool n_ok = n >= 1 && n <= K_max;
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
     tok[i] = i < K_max ? tokens[row + i] : -1;
     // (requested with the other inputs: one trip to memory for all of them)
     const int32_t ts_given = (!partial && i < K_max) ? target_ids[row + i] : -1;
-    const int any_bad = __syncthreads_or(bad ? 1 : 0);
+    const bool any_bad = workgroup_or_128(bad, or_bad);
 
     const int32_t width = depth_cap + 1;
     int32_t* path_b = path + static_cast<size_t>(b) * width;
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(AC_THREADS) void accept_walk_kernel(
     u64 key = (ok && d <= depth_cap) ? ((static_cast<u64>(d) << 8) | static_cast<u64>(255 - i)) : 0;
     u64 wmax = wave_max_u64(key);
     if ((i & 63) == 0) red[i >> 6] = wmax;
-    const int any_over = __syncthreads_or(over);
+    const bool any_over = workgroup_or_128(over != 0, or_over);
     const u64 gmax = red[0] > red[1] ? red[0] : red[1];
     if (key == gmax) {                           // unique: the index is part of the key
         accept_len[b] = d;

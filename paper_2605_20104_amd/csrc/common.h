@@ -22,6 +22,18 @@ inline int32_t check_launch() {
 
 using u64 = unsigned long long;
 
+// OR of a predicate over a workgroup of two wavefronts (the 128-thread kernels): each wavefront
+// puts its ballot's verdict into its own LDS slot, one barrier, everyone reads both slots.  The
+// library's __syncthreads_or costs several hundred cycles more, which these launch-latency-bound
+// kernels notice.  `slots` is LDS, two words, not used for anything else until the next barrier;
+// the barrier also orders every LDS write made before the call.
+__device__ __forceinline__ bool workgroup_or_128(bool pred, int32_t* slots) {
+    const bool wave_any = __builtin_amdgcn_ballot_w64(pred) != 0;
+    if ((threadIdx.x & 63) == 0) slots[threadIdx.x >> 6] = wave_any ? 1 : 0;
+    __syncthreads();
+    return (slots[0] | slots[1]) != 0;
+}
+
 // v from the lane that the DPP control names (0xB1: lane ^ 1, 0x4E: lane ^ 2, 0x141: mirror
 // within 8 lanes, 0x140: mirror within 16 lanes), both halves of the 64-bit value.
 template <int DPP_CTRL>

@@ -38,6 +38,7 @@ __global__ __launch_bounds__(PS_THREADS) void prune_select_kernel(
     __shared__ float c_tau[GRAFT_MAX_CHECKPOINTS];
     __shared__ unsigned gates_open, any_deep, orphan;
     __shared__ int32_t n_cand_s;
+    __shared__ int32_t or_bad[2];
     const size_t row = static_cast<size_t>(b) * K_max;
 
     // every input is requested at once: one trip to memory (the checkpoint parameters included,
@@ -57,7 +58,7 @@ __global__ __launch_bounds__(PS_THREADS) void prune_select_kernel(
     if (n_ok && i < n) bad = (i == 0) ? (p != -1) : (p < 0 || p >= i);
     par[i] = p;
     lqs[i] = (i > 0 && n_ok && i < n) ? lq_in : 0.0f;
-    int any_bad = __syncthreads_or(bad ? 1 : 0);
+    int any_bad = workgroup_or_128(bad, or_bad) ? 1 : 0;
 
     int32_t st = -1, cnt = 0, nret = 0;
     bool kept = false;

@@ -20,6 +20,7 @@ __global__ __launch_bounds__(TM_THREADS) void tree_mask_kernel(
     __shared__ int32_t par[TM_THREADS];
     __shared__ int32_t has_child[TM_THREADS];
     __shared__ int32_t wave_leaves[TM_THREADS / 64];
+    __shared__ int32_t or_bad[2], or_over[2];
 
     const int32_t n = n_nodes[b];
     const int32_t P = prefix_len[b];          // with the other inputs: one trip to memory for all of them
@@ -29,7 +30,7 @@ __global__ __launch_bounds__(TM_THREADS) void tree_mask_kernel(
     if (n_ok && i < n) bad = (i == 0) ? (p != -1) : (p < 0 || p >= i);
     par[i] = p;
     has_child[i] = 0;
-    const int any_bad = __syncthreads_or(bad ? 1 : 0);
+    const bool any_bad = workgroup_or_128(bad, or_bad);
 
     const int32_t width = depth_cap + 1;
     int32_t* paths_b = paths ? paths + static_cast<size_t>(b) * n_leaf_max * width : nullptr;
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(TM_THREADS) void tree_mask_kernel(
         const int32_t used = total < n_leaf_max ? total : n_leaf_max;
         for (int k = used * width + i; k < n_leaf_max * width; k += TM_THREADS) paths_b[k] = -1;
     }
-    const int any_over = __syncthreads_or(overflow);
+    const bool any_over = workgroup_or_128(overflow != 0, or_over);
     if (i == 0) status[b] = any_over ? GRAFT_STATUS_PATH_OVERFLOW : 0;
 }
 
