@@ -49,6 +49,12 @@ __global__ __launch_bounds__(TM_THREADS) void tree_mask_kernel(
         return;
     }
 
+    // the path table starts as all -1 (consecutive addresses, all threads; these stores are on
+    // their way during the walk below); the barriers of the leaf ranking order them before the
+    // leaves' own entries
+    if (paths_b)
+        for (int k = i; k < n_leaf_max * width; k += TM_THREADS) paths_b[k] = -1;
+
     int32_t d = -1;
     if (i < K_max) {
         u64 m0 = 0, m1 = 0;
@@ -75,24 +81,19 @@ __global__ __launch_bounds__(TM_THREADS) void tree_mask_kernel(
         __syncthreads();
         int32_t rank = __popcll(ballot & ((1ull << lane) - 1));
         if (wave == 1) rank += wave_leaves[0];
-        const int32_t total = wave_leaves[0] + wave_leaves[1];
         if (leaf) {
             if (rank >= n_leaf_max) {
                 overflow = 1;                          // dropped
             } else {
                 int32_t* row = paths_b + static_cast<size_t>(rank) * width;
                 if (d > depth_cap) {
-                    overflow = 1;
-                    for (int k = 0; k < width; ++k) row[k] = -1;
+                    overflow = 1;                      // its row stays -1
                 } else {
                     int32_t k = d;
                     for (int32_t j = i; j != -1; j = par[j]) row[k--] = j;
-                    for (k = d + 1; k < width; ++k) row[k] = -1;
                 }
             }
         }
-        const int32_t used = total < n_leaf_max ? total : n_leaf_max;
-        for (int k = used * width + i; k < n_leaf_max * width; k += TM_THREADS) paths_b[k] = -1;
     }
     const bool any_over = workgroup_or_128(overflow != 0, or_over);
     if (i == 0) status[b] = any_over ? GRAFT_STATUS_PATH_OVERFLOW : 0;
