@@ -57,15 +57,24 @@ __global__ __launch_bounds__(TM_THREADS) void tree_mask_kernel(
 
     int32_t d = -1;
     if (i < K_max) {
-        u64 m0 = 0, m1 = 0;
+        // (the walk's dependent chain is the LDS read of the parent alone: the mask bits are set in
+        //  32-bit words, off that chain)
+        unsigned w0 = 0, w1 = 0, w2 = 0, w3 = 0;              // mask bits 0..31, 32..63, 64..95, 96..127
         if (i < n) {
-            for (int32_t j = i; j != -1; j = par[j]) {
-                if (j < 64) m0 |= 1ull << j; else m1 |= 1ull << (j - 64);
+            for (int32_t j = i; j != -1;) {
+                const int32_t up = par[j];
+                const unsigned bit = 1u << (j & 31);
+                const int word = j >> 5;
+                w0 |= word == 0 ? bit : 0u;
+                w1 |= word == 1 ? bit : 0u;
+                w2 |= word == 2 ? bit : 0u;
+                w3 |= word == 3 ? bit : 0u;
                 ++d;
+                j = up;
             }
         }
-        mask_b[i * GRAFT_MASK_WORDS] = m0;
-        mask_b[i * GRAFT_MASK_WORDS + 1] = m1;
+        mask_b[i * GRAFT_MASK_WORDS] = (static_cast<u64>(w1) << 32) | w0;
+        mask_b[i * GRAFT_MASK_WORDS + 1] = (static_cast<u64>(w3) << 32) | w2;
         depth[static_cast<size_t>(b) * K_max + i] = d;
         pos[static_cast<size_t>(b) * K_max + i] = i < n ? P + d : -1;
     }
