@@ -95,4 +95,20 @@ __device__ __forceinline__ float wave_max_f32(float v) {
     return v;
 }
 
+// Maximum over the four lanes l, l + 16, l + 32, l + 48 (the four 16-lane rows of a wavefront),
+// all four get it: the two lane swaps of gfx950, no trip through the LDS crossbar.
+__device__ __forceinline__ float rows_max_f32(float v) {
+    {
+        const unsigned u = __float_as_uint(v);
+        const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+        v = __builtin_fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    {
+        const unsigned u = __float_as_uint(v);
+        const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        v = __builtin_fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    }
+    return v;
+}
+
 }  // namespace graft

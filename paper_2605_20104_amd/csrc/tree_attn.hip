@@ -572,8 +572,7 @@ __device__ __forceinline__ bool set_references(float (&lm)[MB], WaveRows<MB>& w,
 #pragma unroll
     for (int rb = 0; rb < MB; ++rb) {
         float mx = lm[rb];
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = rows_max_f32(mx);
         lm[rb] = mx;                                      // now the row maximum, same in the row's 4 lanes
         raise = raise || (!w.unset(rb) && mx > w.thr[rb]);
     }
@@ -1076,8 +1075,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         float amax = 0.f;
 #pragma unroll
         for (int k = 0; k < 32; ++k) amax = fmaxf(amax, fabsf(ov[k]));
-        amax = fmaxf(amax, __shfl_xor(amax, 16));
-        amax = fmaxf(amax, __shfl_xor(amax, 32));                 // the row's, same in its four lanes
+        amax = rows_max_f32(amax);                                // the row's, same in its four lanes
         // biased exponent of the normalised row maximum, kept where 2^e and 2^-e are normal numbers
         // (a zero row, or values at the ends of the fp32 range, keep a scale they can live with)
         int ex = static_cast<int>((__float_as_uint(amax * inv_l) >> 23) & 0xffu);
