@@ -789,12 +789,21 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     const int n_st = sr.st1 - sr.st0;
 
     // this split's block-table entries: the first 1024 are requested before anything is
-    // stored (one trip for all of them), a longer split takes the plain loop for the rest
+    // stored (one trip for all of them), a longer split takes the plain loop for the rest.
+    // The pages of this wavefront's first two stages are also requested on their own, as
+    // scalars: with them the first transfers can be issued without a trip through LDS and a
+    // barrier.
     int32_t tbv[4];
     const int n_pg = n_st * (AT_STAGE / GRAFT_PAGE_SIZE);
     const int32_t* table = p.block_table + static_cast<size_t>(b) * p.max_pages;
     const int first_pg = sr.st0 * (AT_STAGE / GRAFT_PAGE_SIZE);
     const int last_pg = (sr.total - 1) >> 4;
+    int32_t first_pages[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int pg = first_pg + 4 * u + wave_u;
+        first_pages[u] = (4 * u + wave_u) < n_pg ? table[pg < last_pg ? pg : last_pg] : 0;
+    }
     {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -802,10 +811,9 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             tbv[u] = (tid + u * AT_THREADS) < n_pg ? table[pg < last_pg ? pg : last_pg] : 0;
         }
     }
-    // ---- this wavefront's rows: Q' = bf16(Q * scale * log2 e) into AccVGPRs, O^T to zero.  Done
-    //      here, while the table entries are on their way (Q was requested before them and vector
-    //      memory returns in order): some 700 vector instructions that would otherwise sit
-    //      between the first transfers and the first MFMA.
+    // ---- this wavefront's rows: Q' = bf16(Q * scale * log2 e) into AccVGPRs.  Done here, while
+    //      the table entries are on their way (Q was requested before them and vector memory
+    //      returns in order).
     const float c_log2 = p.scale_log2e;
     WaveRows<MB> w;
     static_for<0, MB>([&](auto rb_) {
@@ -818,20 +826,10 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         w.thr[rb] = -INFINITY;
         w.thr_min = -INFINITY;
         w.negm[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if constexpr (rb >= L_IN_ACC) w.lsum_v = floatx4{0.f, 0.f, 0.f, 0.f};
-        else
-            static_for<0, 4>([&](auto k_) {
-                GRAFT_CONST(k, k_);
-                acc_set<l_reg<MB>(rb) + k>(0.0f);
-            });
-        static_for<0, 32>([&](auto k_) {
-            GRAFT_CONST(k, k_);
-            acc_set<32 * rb + k>(0.0f);
-        });
     });
-    // the first pipeline step multiplies zero probabilities with whatever buffer 3 holds: make it zeros
-    for (int k = tid; k < AT_STAGE * AT_ROW_BYTES / 16; k += AT_THREADS)
-        reinterpret_cast<uint4*>(&kv[AT_NBUF - 1][AT_STAGE * AT_ROW_BYTES])[k] = uint4{0u, 0u, 0u, 0u};
+    // Everything that came from memory goes to LDS now, so that no load the compiler tracks is
+    // outstanding when the first transfers are issued (it counts its own loads only, and a
+    // wait for one of them behind the transfers would wait for the transfers as well).
     if (tid < n_mask_words) Ms[tid] = mw0;
     if (tid + AT_THREADS < n_mask_words) Ms[tid + AT_THREADS] = mw1;
 #pragma unroll
@@ -841,7 +839,6 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         const int pg = first_pg + k;
         Tb[k] = table[pg < last_pg ? pg : last_pg];
     }
-    __syncthreads();
 
     // ---- stage pipeline: stage k (split-local) lives in kv[k & 3]; its loads are issued two
     //      stages ahead.  advance(k) = wait for this wavefront's loads of stage k (the next
@@ -862,13 +859,9 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         koff[j] = row_off + kchunk * 16;
         voff[j] = row_off + vchunk * 16;
     }
-    int tb_next = Tb[wave_u];       // stages are issued in order: the next stage's table entry is read one stage early
-    auto issue_stage = [&](int k) {
+    auto issue_page = [&](int k, int page) {
         const unsigned buf = kv_base + (k & (AT_NBUF - 1)) * AT_STAGE_BYTES + wave_u * 4096;
         const int t_page = (sr.st0 + k) * AT_STAGE + 16 * wave_u;   // first token of this wavefront's page
-        const int page = __builtin_amdgcn_readfirstlane(tb_next);
-        const int nxt = (k + 1) * 4 + wave_u;
-        tb_next = Tb[nxt < AT_MAX_SPLIT_PAGES ? nxt : AT_MAX_SPLIT_PAGES - 1];
         const int64_t page_off = (static_cast<int64_t>(page) * p.page_stride + static_cast<int64_t>(g) * p.head_stride) * 2;
         const unsigned char* kp = static_cast<const unsigned char*>(p.k) + page_off;
         const unsigned char* vp = static_cast<const unsigned char*>(p.v) + page_off;
@@ -894,6 +887,46 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             }
         }
     };
+    // The first stage starts here, before the rest of the set-up: its flight time covers the
+    // zeroing of the accumulators and the barrier.  The second follows after the zeroing: all
+    // workgroups start at the same time, and the memory system delivers their first stages
+    // sooner when the requests for the second ones are not queued in between.
+    int next_issue = 0;                          // stages are issued in order, each once
+    if (n_st > 0) {
+        issue_page(0, __builtin_amdgcn_readfirstlane(first_pages[0]));
+        next_issue = 1;
+    }
+
+    // O^T and the row sums to zero
+    static_for<0, MB>([&](auto rb_) {
+        GRAFT_CONST(rb, rb_);
+        if constexpr (rb >= L_IN_ACC) w.lsum_v = floatx4{0.f, 0.f, 0.f, 0.f};
+        else
+            static_for<0, 4>([&](auto k_) {
+                GRAFT_CONST(k, k_);
+                acc_set<l_reg<MB>(rb) + k>(0.0f);
+            });
+        static_for<0, 32>([&](auto k_) {
+            GRAFT_CONST(k, k_);
+            acc_set<32 * rb + k>(0.0f);
+        });
+    });
+    // the first pipeline step multiplies zero probabilities with whatever buffer 3 holds: make it zeros
+    for (int k = tid; k < AT_STAGE * AT_ROW_BYTES / 16; k += AT_THREADS)
+        reinterpret_cast<uint4*>(&kv[AT_NBUF - 1][AT_STAGE * AT_ROW_BYTES])[k] = uint4{0u, 0u, 0u, 0u};
+    if (n_st > 1) {
+        issue_page(1, __builtin_amdgcn_readfirstlane(first_pages[1]));
+        next_issue = 2;
+    }
+    lds_barrier();                               // (LDS only: the transfers stay in flight)
+
+    int tb_next = Tb[2 * 4 + wave_u];            // the next stage's table entry is read one stage early
+    auto issue_stage = [&](int k) {
+        const int page = __builtin_amdgcn_readfirstlane(tb_next);
+        const int nxt = (k + 1) * 4 + wave_u;
+        tb_next = Tb[nxt < AT_MAX_SPLIT_PAGES ? nxt : AT_MAX_SPLIT_PAGES - 1];
+        issue_page(k, page);
+    };
     // arrive(k): wait for this wavefront's transfers of stage k (those of stage k + 1 stay in
     // flight) and meet the other wavefronts.  After it stage k can be read and the buffer of
     // stage k + 2 (last read in step k - 1) can be refilled.  advance(k) also starts stage k + 2.
@@ -908,7 +941,6 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     // the barrier; the other two issue in the middle of the stage (the target buffer is free
     // during the whole stage), when the first two are computing.
     const bool early_wave = wave_u < 2;
-    int next_issue = 0;                          // stages are issued in order, each once
     auto issue_upto = [&](int s) {
         while (next_issue <= s && next_issue < n_st) issue_stage(next_issue++);
     };
@@ -916,11 +948,9 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         arrive(k);
         if (early_wave) issue_upto(k + 2);
     };
-    issue_upto(1);
 
-    // Every load the compiler tracks (lengths, Q, masks, table) was consumed above, before the
-    // first transfer was issued; only the transfers of stages 0 and 1 are in flight, and the
-    // first advance() waits for stage 0 alone.
+    // Only the transfers of stages 0 and 1 are in flight here, and the first advance() waits
+    // for stage 0 alone.
     GRAFT_MFMA_SETTLE();
 
     uintx4 ones_bits;
