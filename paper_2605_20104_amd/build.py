@@ -13,6 +13,7 @@ CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libgraft.so")
+LIB_TIMING = os.path.join(PKG, "libgraft_timing.so")     # the same library with the attention kernel's time stamps
 SOURCES = ["api.hip", "retrieve.hip", "tree_mask.hip", "tree_attn.hip", "accept.hip", "matrix.hip", "kv_compact.hip", "prune.hip"]
 
 # packed-fp32 code generation is switched off for every device compile; VGPR spills must not
@@ -35,6 +36,10 @@ ATTN_ASM = os.path.join(OBJ_DIR, "tree_attn-hip-amdgcn-amd-amdhsa-gfx950.s")
 
 def _compile(src: str, extra):
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+    return _compile_to(src, extra, obj)
+
+
+def _compile_to(src: str, extra, obj: str):
     keep = ["-save-temps=obj"] if src == "tree_attn.hip" else []    # keeps the device assembly for the check below
     cmd = [_hipcc(), *HIPCC_FLAGS, *extra, *keep, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -179,6 +184,27 @@ def check_attention_asm(asm_text: str):
     return problems
 
 
+def _check_and_clean(asm_path: str, what: str):
+    with open(asm_path) as f:
+        problems = check_attention_asm(f.read())
+    for name in os.listdir(OBJ_DIR):             # the other intermediate files are not needed
+        if name.startswith("tree_attn") and not name.endswith((".o", "gfx950.s")) or name.endswith(".hipfb"):
+            os.remove(os.path.join(OBJ_DIR, name))
+    if problems:
+        raise RuntimeError("%s: the generated assembly breaks a rule of the hand-scheduled kernel:\n  "
+                           % what + "\n  ".join(problems[:20]))
+
+
+def _link(objects, lib: str) -> str:
+    tmp = lib + ".tmp%d" % os.getpid()
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objects, "-o", tmp]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + r.stdout)
+    os.replace(tmp, lib)
+    return lib
+
+
 def build(verbose: bool = False, extra_flags=()) -> str:
     """Compile every HIP source and link libgraft.so next to the package. Always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
@@ -188,22 +214,37 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         for _, w in results:
             if w:
                 print(w)
-    with open(ATTN_ASM) as f:
+    _check_and_clean(ATTN_ASM, "tree_attn.hip")
+    return _link([o for o, _ in results], LIB)
+
+
+def build_timing(verbose: bool = False) -> str:
+    """libgraft_timing.so: the library with the attention kernel compiled with -DGRAFT_ATTN_STAMPS
+    (time stamps per workgroup, read by `python -m paper_2605_20104_amd.timing`).  The other
+    objects are those of the last build(); the stamped kernels pass the same assembly check."""
+    others = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES if s != "tree_attn.hip"]
+    if not all(os.path.exists(o) for o in others):
+        build(verbose)
+    src_dir = os.path.join(OBJ_DIR, "timing")
+    os.makedirs(src_dir, exist_ok=True)
+    obj = os.path.join(src_dir, "tree_attn.o")
+    _, warn = _compile_to("tree_attn.hip", ["-DGRAFT_ATTN_STAMPS"], obj)
+    if verbose and warn:
+        print(warn)
+    asm = os.path.join(src_dir, "tree_attn-hip-amdgcn-amd-amdhsa-gfx950.s")
+    with open(asm) as f:
         problems = check_attention_asm(f.read())
-    for name in os.listdir(OBJ_DIR):             # the other intermediate files are not needed
-        if name.startswith("tree_attn") and not name.endswith((".o", "gfx950.s")) or name.endswith(".hipfb"):
-            os.remove(os.path.join(OBJ_DIR, name))
+    for name in os.listdir(src_dir):
+        if not name.endswith((".o", "gfx950.s")):
+            os.remove(os.path.join(src_dir, name))
     if problems:
-        raise RuntimeError("tree_attn.hip: the generated assembly breaks a rule of the hand-scheduled kernel:\n  "
-                           + "\n  ".join(problems[:20]))
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *[o for o, _ in results], "-o", tmp]
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stdout)
-    os.replace(tmp, LIB)
-    return LIB
+        raise RuntimeError("tree_attn.hip (timing build): the generated assembly breaks a rule of the "
+                           "hand-scheduled kernel:\n  " + "\n  ".join(problems[:20]))
+    return _link([obj, *others], LIB_TIMING)
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, extra_flags=sys.argv[1:]))
+    flags = [a for a in sys.argv[1:] if a != "--timing"]
+    print(build(verbose=True, extra_flags=flags))
+    if "--timing" in sys.argv[1:]:
+        print(build_timing(verbose=True))

@@ -87,7 +87,56 @@ struct AttnParams {
     int32_t g_magic;    // ceil(2^16 / G): r / G == (r * g_magic) >> 16 for r < 4096, G <= 16
     float scale;        // softmax scale
     float scale_log2e;  // scale * log2(e)
+#ifdef GRAFT_ATTN_STAMPS
+    unsigned long long* stamps;   // timing build: AT_STAMPS values per workgroup, or null
+#endif
 };
+
+// Timing build (-DGRAFT_ATTN_STAMPS, a library of its own: see build.py): the MFMA kernel
+// records when each workgroup passed the points below and writes them to a buffer the caller
+// registered with graft_attn_stamp_buffer().  Times are values of the 100 MHz real-time counter
+// (the first absolute, the others relative to it), two entries are the core-clock counter at
+// both ends of the stage loop, which gives the clock the loop ran at.  Without the flag the
+// macros are empty and the kernel is unchanged.
+constexpr int AT_STAMPS = 16;
+enum AttnStamp {
+    AT_TS_START = 0,          // first instruction of the workgroup (absolute)
+    AT_TS_LENGTHS = 1,        // lengths known
+    AT_TS_TABLE_REQ = 2,      // block-table entries requested
+    AT_TS_Q_DONE = 3,         // Q converted
+    AT_TS_TABLE_LDS = 4,      // table and masks stored to LDS
+    AT_TS_STAGE0_REQ = 5,     // transfers of stage 0 issued
+    AT_TS_ZEROED = 6,         // accumulators zeroed, stage 1 issued (in front of the barrier)
+    AT_TS_LOOP = 7,           // stage loop entered
+    AT_TS_STAGE0 = 8,         // first stage arrived
+    AT_TS_LOOP_END = 9,       // stage loop left
+    AT_TS_END = 10,           // results written
+    AT_TS_CYCLES_LOOP = 11,   // core-clock counter at AT_TS_LOOP
+    AT_TS_CYCLES_END = 12,    // core-clock counter at AT_TS_LOOP_END
+    AT_TS_STAGES = 13,        // stages of this workgroup
+    AT_TS_VALID = 14,         // 1
+};
+#ifdef GRAFT_ATTN_STAMPS
+#define GRAFT_STAMPS_BEGIN()                                \
+    unsigned long long at_stamp[AT_STAMPS] = {};            \
+    at_stamp[AT_TS_START] = __builtin_amdgcn_s_memrealtime()
+#define GRAFT_STAMP(k) (at_stamp[k] = __builtin_amdgcn_s_memrealtime() - at_stamp[AT_TS_START])
+#define GRAFT_STAMP_CYCLES(k) (at_stamp[k] = __builtin_readcyclecounter())
+#define GRAFT_STAMPS_WRITE(p, n_stages)                                                     \
+    do {                                                                                    \
+        GRAFT_STAMP(AT_TS_END);                                                             \
+        at_stamp[AT_TS_STAGES] = static_cast<unsigned long long>(n_stages);                 \
+        at_stamp[AT_TS_VALID] = 1;                                                          \
+        if (threadIdx.x == 0 && (p).stamps)                                                 \
+            for (int at_k = 0; at_k < AT_STAMPS; ++at_k)                                    \
+                (p).stamps[static_cast<size_t>(blockIdx.x) * AT_STAMPS + at_k] = at_stamp[at_k]; \
+    } while (0)
+#else
+#define GRAFT_STAMPS_BEGIN() ((void)0)
+#define GRAFT_STAMP(k) ((void)0)
+#define GRAFT_STAMP_CYCLES(k) ((void)0)
+#define GRAFT_STAMPS_WRITE(p, n_stages) ((void)0)
+#endif
 
 __device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
     return __uint_as_float(static_cast<unsigned>(b) << 16);
@@ -731,6 +780,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     __shared__ int32_t Tb[AT_MAX_SPLIT_PAGES];                         // this split's block-table entries
 
     reserve_acc_registers<MB>();
+    GRAFT_STAMPS_BEGIN();
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, lg = lane >> 4;
@@ -787,6 +837,10 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     sr.st1 = (sr.st0 + spt) < n_stages ? (sr.st0 + spt) : n_stages;
     if (sr.st1 < sr.st0) sr.st1 = sr.st0;
     const int n_st = sr.st1 - sr.st0;
+#ifdef GRAFT_ATTN_STAMPS
+    asm volatile("" : : "s"(n_st));              // (the stamp is taken when the lengths are there)
+#endif
+    GRAFT_STAMP(AT_TS_LENGTHS);
 
     // this split's block-table entries: the first 1024 are requested before anything is
     // stored (one trip for all of them), a longer split takes the plain loop for the rest.
@@ -811,6 +865,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
             tbv[u] = (tid + u * AT_THREADS) < n_pg ? table[pg < last_pg ? pg : last_pg] : 0;
         }
     }
+    GRAFT_STAMP(AT_TS_TABLE_REQ);
     // ---- this wavefront's rows: Q' = bf16(Q * scale * log2 e) into AccVGPRs.  Done here, while
     //      the table entries are on their way (Q was requested before them and vector memory
     //      returns in order).
@@ -827,6 +882,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         w.thr_min = -INFINITY;
         w.negm[rb] = floatx4{0.f, 0.f, 0.f, 0.f};
     });
+    GRAFT_STAMP(AT_TS_Q_DONE);
     // Everything that came from memory goes to LDS now, so that no load the compiler tracks is
     // outstanding when the first transfers are issued (it counts its own loads only, and a
     // wait for one of them behind the transfers would wait for the transfers as well).
@@ -892,10 +948,12 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     // workgroups start at the same time, and the memory system delivers their first stages
     // sooner when the requests for the second ones are not queued in between.
     int next_issue = 0;                          // stages are issued in order, each once
+    GRAFT_STAMP(AT_TS_TABLE_LDS);
     if (n_st > 0) {
         issue_page(0, __builtin_amdgcn_readfirstlane(first_pages[0]));
         next_issue = 1;
     }
+    GRAFT_STAMP(AT_TS_STAGE0_REQ);
 
     // O^T and the row sums to zero
     static_for<0, MB>([&](auto rb_) {
@@ -918,6 +976,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         issue_page(1, __builtin_amdgcn_readfirstlane(first_pages[1]));
         next_issue = 2;
     }
+    GRAFT_STAMP(AT_TS_ZEROED);
     lds_barrier();                               // (LDS only: the transfers stay in flight)
 
     int tb_next = Tb[2 * 4 + wave_u];            // the next stage's table entry is read one stage early
@@ -979,6 +1038,8 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
 #pragma unroll
         for (int c = 0; c < 2; ++c) xb[rb][c] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 
+    GRAFT_STAMP(AT_TS_LOOP);
+    GRAFT_STAMP_CYCLES(AT_TS_CYCLES_LOOP);
     const int n_sub = 2 * n_st;
     int j = 0;                 // sub-tile whose exponents are pending when the fast loop is left
     bool slow = false;
@@ -988,6 +1049,9 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         // (transfers of stage k + 2: see advance(); issuing them inside the MFMA regions was
         //  measured slower, a transfer issued while MFMAs are in flight stalls the wavefront)
         if (live) advance(k);
+#ifdef GRAFT_ATTN_STAMPS
+        if (k == 0) GRAFT_STAMP(AT_TS_STAGE0);
+#endif
         const unsigned char* cur = kv[k & (AT_NBUF - 1)];
         const unsigned char* prev = kv[(k - 1) & (AT_NBUF - 1)];
         const int t0 = (sr.st0 + k) * AT_STAGE;
@@ -1068,6 +1132,8 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         }
     }
     GRAFT_MFMA_SETTLE();
+    GRAFT_STAMP(AT_TS_LOOP_END);
+    GRAFT_STAMP_CYCLES(AT_TS_CYCLES_END);
 
     if (p.n_splits == 1) {
         // ---- one split: this workgroup holds the whole result of its rows
@@ -1077,6 +1143,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         int lane_out = lane;
         asm volatile("" : "+v"(lane_out));
         store_rows<MB>(p, w, b, g, r_base, sr.n, lane_out);
+        GRAFT_STAMPS_WRITE(p, n_st);
         return;
     }
     // ---- partial results.  Per row and split: the reference max m (log2 units), the row sum l
@@ -1125,6 +1192,7 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
         if (lg == 0)
             *reinterpret_cast<floatx4*>(p.ws_ml + (part + r0 + l16) * 4) = floatx4{w.m_ref(rb), l, pow2e, 0.f};
     });
+    GRAFT_STAMPS_WRITE(p, n_st);
 }
 
 // Merge the splits of two adjacent 16-row x 16-dim output tiles:
@@ -1372,6 +1440,10 @@ static int device_compute_units() {
     return cached;
 }
 
+#ifdef GRAFT_ATTN_STAMPS
+static thread_local int g_force_splits = 0, g_force_row_tiles = 0;
+#endif
+
 // Launch shape of the MFMA path.  One workgroup per compute unit is resident at a time, so
 // the job runs in ceil(workgroups / CUs) rounds, each as long as one workgroup's pass: a
 // fixed part (set-up, Q conversion, writing the partial results) plus its stages.  The
@@ -1410,6 +1482,15 @@ static AttnPlan make_plan(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
             }
         }
     }
+#ifdef GRAFT_ATTN_STAMPS
+    // timing build: a plan held fixed by the caller (to compare runs that differ in nothing else)
+    if (g_force_splits >= (min_splits < 1 ? 1 : min_splits) && g_force_splits <= (stages < AT_MAX_SPLITS ? stages : AT_MAX_SPLITS) &&
+        g_force_row_tiles >= rt_min && g_force_row_tiles <= rt_max) {
+        pl.n_splits = g_force_splits;
+        pl.n_row_tiles = g_force_row_tiles;
+        pl.mb = (R + pl.n_row_tiles * rows_per_mb - 1) / (pl.n_row_tiles * rows_per_mb);
+    }
+#endif
     pl.r_pad = pl.n_row_tiles * pl.mb * rows_per_mb;
     if (pl.n_splits > 1) {                                       // one split needs no workspace and no merge
         const size_t rows = static_cast<size_t>(B) * Hkv * pl.n_splits * pl.r_pad;
@@ -1431,6 +1512,10 @@ static bool attn_shape_ok(int32_t B, int32_t K_max, int32_t Hq, int32_t Hkv, int
 static thread_local hipEvent_t* g_prof_start = nullptr;
 static thread_local hipEvent_t* g_prof_stop = nullptr;
 static thread_local int32_t g_prof_n = 0, g_prof_i = 0;
+#ifdef GRAFT_ATTN_STAMPS
+static thread_local unsigned long long* g_stamps = nullptr;      // device buffer of the timing build
+static thread_local size_t g_stamps_bytes = 0;
+#endif
 
 template <class Kernel>
 static void launch_main(Kernel kernel, dim3 grid, dim3 block, hipStream_t s, const AttnParams& p) {
@@ -1459,6 +1544,26 @@ extern "C" int32_t graft_attn_profile_events(void** start_events, void** stop_ev
     graft::g_prof_i = 0;
     return GRAFT_OK;
 }
+
+#ifdef GRAFT_ATTN_STAMPS
+// Timing build only (not part of the library's interface): device buffer that the MFMA kernel of
+// this host thread's following graft_tree_attn calls fills with AT_STAMPS 64-bit values per
+// workgroup; a call whose grid does not fit the buffer records nothing.  Null switches it off.
+extern "C" int32_t graft_attn_stamp_buffer(void* device_buffer, size_t bytes) {
+    graft::g_stamps = static_cast<unsigned long long*>(device_buffer);
+    graft::g_stamps_bytes = device_buffer ? bytes : 0;
+    return GRAFT_OK;
+}
+extern "C" int32_t graft_attn_stamp_count(void) { return graft::AT_STAMPS; }
+// Holds the launch plan of this host thread's following calls (workspace query included) at
+// n_splits splits and n_row_tiles row tiles where the shape allows them; zeros give the plan
+// back to the cost model.
+extern "C" int32_t graft_attn_force_plan(int32_t n_splits, int32_t n_row_tiles) {
+    graft::g_force_splits = n_splits;
+    graft::g_force_row_tiles = n_row_tiles;
+    return GRAFT_OK;
+}
+#endif
 
 extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const void* v_cache,
                                    int64_t page_stride, int64_t token_stride, int64_t head_stride,
@@ -1506,6 +1611,9 @@ extern "C" int32_t graft_tree_attn(const void* q, const void* k_cache, const voi
     p.ws_ml = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + pl.ws_o_bytes);
     const int64_t n_units = static_cast<int64_t>(B) * Hkv * pl.n_splits;
     dim3 grid(static_cast<unsigned>(((n_units + 7) / 8) * 8 * pl.n_row_tiles));
+#ifdef GRAFT_ATTN_STAMPS
+    p.stamps = static_cast<size_t>(grid.x) * AT_STAMPS * sizeof(unsigned long long) <= g_stamps_bytes ? g_stamps : nullptr;
+#endif
     switch (pl.mb) {
         case 1: launch_main(tree_attn_mfma_kernel<1>, grid, dim3(AT_THREADS), s, p); break;
         case 2: launch_main(tree_attn_mfma_kernel<2>, grid, dim3(AT_THREADS), s, p); break;

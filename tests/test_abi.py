@@ -34,6 +34,29 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(g.EXPORTED_SYMBOLS) == names
 
 
+def test_timing_build_is_the_same_interface_plus_its_own_calls(lib):
+    """libgraft_timing.so (the attention kernel with time stamps) exports everything the header
+    declares and the three calls of the timing tool; the product library has none of those."""
+    from paper_2605_20104_amd import build
+    if not os.path.exists(build.LIB_TIMING):
+        pytest.skip("libgraft_timing.so is not built (python -m paper_2605_20104_amd.build --timing)")
+    timing = ctypes.CDLL(build.LIB_TIMING)
+    for n in declared_functions():
+        assert getattr(timing, n) is not None
+    for n in ("graft_attn_stamp_buffer", "graft_attn_stamp_count", "graft_attn_force_plan"):
+        assert getattr(timing, n) is not None
+        assert not hasattr(lib, n), n
+    assert timing.graft_attn_stamp_count() == 16
+    # a held plan changes the workspace the same call asks for, and zeros give it back
+    args = (1, 64, 40, 8, 128, 2052, 1)
+    timing.graft_tree_attn_workspace_bytes.restype = ctypes.c_size_t
+    auto = timing.graft_tree_attn_workspace_bytes(*args)
+    timing.graft_attn_force_plan(16, 1)
+    held = timing.graft_tree_attn_workspace_bytes(*args)
+    timing.graft_attn_force_plan(0, 0)
+    assert held != auto and timing.graft_tree_attn_workspace_bytes(*args) == auto
+
+
 def test_header_constants_match_binding():
     import paper_2605_20104_amd as g
     text = open(HEADER).read()
