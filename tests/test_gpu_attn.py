@@ -363,3 +363,66 @@ def test_many_splits_agree_with_a_single_split():
     ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], "bf16", att["strides"],
                            att["block_table"], p1, n1, parent, w1.Hq, w1.Hkv, w1.D, 16, att["scale"])
     assert np.abs(one - ref.astype(np.float32)).max() <= TOL_BF16 and np.abs(many[:1] - ref.astype(np.float32)).max() <= TOL_BF16
+
+
+def test_timing_build_gives_the_same_rows_and_ordered_stamps():
+    """The timing build (the kernel with time stamps, libgraft_timing.so) computes what the product
+    library computes, bit for bit, with a plan of its own choice and with a held plan against the
+    oracle; the stamps of every workgroup that ran are in order."""
+    import ctypes
+    from paper_2605_20104_amd import build
+    import os
+    if not os.path.exists(build.LIB_TIMING):
+        pytest.skip("libgraft_timing.so is not built (python -m paper_2605_20104_amd.build --timing)")
+    timing = ctypes.CDLL(build.LIB_TIMING)
+    for name in ("graft_tree_attn", "graft_tree_attn_workspace_bytes"):
+        f = getattr(timing, name)
+        f.restype, f.argtypes = graft._SIGNATURES[name]
+    timing.graft_attn_stamp_buffer.restype, timing.graft_attn_stamp_buffer.argtypes = ctypes.c_int32, [ctypes.c_void_p, ctypes.c_size_t]
+    timing.graft_attn_force_plan.restype, timing.graft_attn_force_plan.argtypes = ctypes.c_int32, [ctypes.c_int32, ctypes.c_int32]
+    n_stamps = timing.graft_attn_stamp_count()
+
+    w = shape_workload(2, 40, 16, 4, 128, 3000)
+    rng = np.random.default_rng(5)
+    att = inputs.make_attention_inputs(w, seed=5)
+    parent = np.stack([inputs.random_recursive_tree(rng, w.K, 8) for _ in range(w.B)])
+    n_nodes, prefix = np.array([40, 33], np.int32), np.array([3000, 1777], np.int32)
+    mask = gpu_mask(parent, n_nodes, prefix)
+    q, k, v = (dev(att[x][0], "bf16") for x in ("q", "k_cache", "v_cache"))
+    table, d_prefix, d_nodes = dev(att["block_table"]), dev(prefix), dev(n_nodes)
+    product = graft.graft_tree_attn(q, k, v, att["strides"], table, d_prefix, d_nodes, mask, w.Hkv, att["scale"])
+
+    def run_timing():
+        shape = (w.B, w.K, w.Hq, w.Hkv, w.D, table.shape[1], graft.GRAFT_BF16)
+        need = timing.graft_tree_attn_workspace_bytes(*shape)
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        stamps = torch.zeros(4096 * n_stamps, dtype=torch.int64, device="cuda")
+        out = torch.empty_like(q)
+        timing.graft_attn_stamp_buffer(stamps.data_ptr(), stamps.numel() * 8)
+        rc = timing.graft_tree_attn(
+            q.data_ptr(), k.data_ptr(), v.data_ptr(), int(att["strides"]["page"]), int(att["strides"]["token"]),
+            int(att["strides"]["head"]), table.data_ptr(), table.shape[1], d_prefix.data_ptr(), d_nodes.data_ptr(),
+            mask.data_ptr(), w.B, w.K, w.Hq, w.Hkv, w.D, graft.GRAFT_PAGE_SIZE, float(att["scale"]), graft.GRAFT_BF16,
+            out.data_ptr(), ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        timing.graft_attn_stamp_buffer(None, 0)
+        assert rc == 0
+        st = stamps.cpu().numpy().reshape(4096, n_stamps)
+        return out, st[st[:, 14] == 1]
+
+    out, st = run_timing()
+    assert torch.equal(out.view(torch.int16), product.view(torch.int16))
+    assert len(st) > 0
+    assert (np.diff(st[:, 1:11], axis=1) >= 0).all()          # the points of a workgroup's life, in order
+    assert (st[:, 12] > st[:, 11]).all() and (st[:, 10] < 100000).all()   # cycles advance; under a millisecond
+
+    timing.graft_attn_force_plan(3, 1)                         # three splits, all rows in one tile
+    try:
+        held, st_held = run_timing()
+    finally:
+        timing.graft_attn_force_plan(0, 0)
+    assert len(st_held) == w.B * w.Hkv * 3
+    ref = oracle.tree_attn(att["q"][0], att["k_cache"][0], att["v_cache"][0], w.dtype, att["strides"],
+                           att["block_table"], prefix, n_nodes, parent, w.Hq, w.Hkv, w.D, w.page_size, att["scale"])
+    err = np.abs(host(held).astype(np.float64) - np.asarray(ref, np.float64))
+    assert err[0].max() <= TOL_BF16 and err[1, :33].max() <= TOL_BF16
