@@ -98,7 +98,7 @@ struct AttnParams {
 // (the first absolute, the others relative to it), two entries are the core-clock counter at
 // both ends of the stage loop, which gives the clock the loop ran at.  Without the flag the
 // macros are empty and the kernel is unchanged.
-constexpr int AT_STAMPS = 16;
+constexpr int AT_STAMPS = 24;
 enum AttnStamp {
     AT_TS_START = 0,          // first instruction of the workgroup (absolute)
     AT_TS_LENGTHS = 1,        // lengths known
@@ -115,6 +115,8 @@ enum AttnStamp {
     AT_TS_CYCLES_END = 12,    // core-clock counter at AT_TS_LOOP_END
     AT_TS_STAGES = 13,        // stages of this workgroup
     AT_TS_VALID = 14,         // 1
+    AT_TS_WAIT_CYCLES = 15,   // core-clock cycles wavefront 0 waited for its transfers of a stage, summed
+    AT_TS_BARRIER_CYCLES = 16,  // ... and at the stage barriers (reading the counter costs some 50 cycles itself)
 };
 #ifdef GRAFT_ATTN_STAMPS
 #define GRAFT_STAMPS_BEGIN()                                \
@@ -122,6 +124,9 @@ enum AttnStamp {
     at_stamp[AT_TS_START] = __builtin_amdgcn_s_memrealtime()
 #define GRAFT_STAMP(k) (at_stamp[k] = __builtin_amdgcn_s_memrealtime() - at_stamp[AT_TS_START])
 #define GRAFT_STAMP_CYCLES(k) (at_stamp[k] = __builtin_readcyclecounter())
+#define GRAFT_SPAN_BEGIN() const unsigned long long at_span0 = __builtin_readcyclecounter()
+#define GRAFT_SPAN_SPLIT(k) const unsigned long long at_span1 = __builtin_readcyclecounter(); at_stamp[k] += at_span1 - at_span0
+#define GRAFT_SPAN_END(k) (at_stamp[k] += __builtin_readcyclecounter() - at_span1)
 #define GRAFT_STAMPS_WRITE(p, n_stages)                                                     \
     do {                                                                                    \
         GRAFT_STAMP(AT_TS_END);                                                             \
@@ -135,6 +140,9 @@ enum AttnStamp {
 #define GRAFT_STAMPS_BEGIN() ((void)0)
 #define GRAFT_STAMP(k) ((void)0)
 #define GRAFT_STAMP_CYCLES(k) ((void)0)
+#define GRAFT_SPAN_BEGIN() ((void)0)
+#define GRAFT_SPAN_SPLIT(k) ((void)0)
+#define GRAFT_SPAN_END(k) ((void)0)
 #define GRAFT_STAMPS_WRITE(p, n_stages) ((void)0)
 #endif
 
@@ -990,9 +998,12 @@ __global__ __launch_bounds__(AT_THREADS) void tree_attn_mfma_kernel(AttnParams p
     // flight) and meet the other wavefronts.  After it stage k can be read and the buffer of
     // stage k + 2 (last read in step k - 1) can be refilled.  advance(k) also starts stage k + 2.
     auto arrive = [&](int k) {
+        GRAFT_SPAN_BEGIN();
         if (k + 1 < n_st) GRAFT_WAIT_VMCNT(AT_LOADS_PER_STAGE);
         else GRAFT_WAIT_VMCNT(0);
+        GRAFT_SPAN_SPLIT(AT_TS_WAIT_CYCLES);
         lds_barrier();
+        GRAFT_SPAN_END(AT_TS_BARRIER_CYCLES);
     };
     // The compute unit's address path takes about 16 cycles per 1 KB transfer, and a wavefront
     // that issues waits for its turn: four wavefronts issuing their 8 transfers at the same

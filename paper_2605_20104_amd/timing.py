@@ -102,6 +102,10 @@ def main(argv=None):
     clk = cyc / (loop_us * 1e3)
     print("  stage loop: %.1f us, %.1f k cycles, clock %.3f GHz (p10 %.3f, p90 %.3f)"
           % (loop_us.mean(), cyc.mean() / 1e3, clk.mean(), *np.percentile(clk, [10, 90])))
+    if n_stamps > 16:
+        n_full = st[full, 13]
+        print("  wavefront 0, per stage: %.0f cycles waiting for its transfers, %.0f at the stage barrier"
+              % ((st[full, 15] / n_full).mean(), (st[full, 16] / n_full).mean()))
     start = (st[:, 0] - st[:, 0].min()) / 100.0
     end = start + st[:, 10] / 100.0
     print("  workgroups start within %.2f us; the last one ends %.2f us after the first one started" % (start.max(), end.max()))

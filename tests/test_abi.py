@@ -46,7 +46,7 @@ def test_timing_build_is_the_same_interface_plus_its_own_calls(lib):
     for n in ("graft_attn_stamp_buffer", "graft_attn_stamp_count", "graft_attn_force_plan"):
         assert getattr(timing, n) is not None
         assert not hasattr(lib, n), n
-    assert timing.graft_attn_stamp_count() == 16
+    assert timing.graft_attn_stamp_count() == 24
     # a held plan changes the workspace the same call asks for, and zeros give it back
     args = (1, 64, 40, 8, 128, 2052, 1)
     timing.graft_tree_attn_workspace_bytes.restype = ctypes.c_size_t
