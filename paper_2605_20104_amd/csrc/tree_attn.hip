@@ -1557,6 +1557,59 @@ extern "C" int32_t graft_attn_profile_events(void** start_events, void** stop_ev
 }
 
 #ifdef GRAFT_ATTN_STAMPS
+namespace graft {
+// Timing build only: what the matrix cores of this chip deliver on a plain stream of independent
+// v_mfma_f32_16x16x32_bf16 with operands of a given distribution (the clock under such a load
+// depends on what the operands hold).  Every wavefront loads eight operands (64 lanes x 16 bytes
+// each, the same for all wavefronts) and runs iters rounds of eight MFMAs on eight accumulators;
+// every wavefront records real-time and core-clock counters around its loop (the wavefronts of a
+// SIMD do not share the matrix core evenly: the oldest one runs first).
+__global__ __launch_bounds__(1024) void mfma_calibration_kernel(const uintx4* __restrict__ operands, float* __restrict__ sink,
+                                                               int iters, unsigned long long* __restrict__ stamps) {
+    const int lane = threadIdx.x & 63;
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        a[j] = __builtin_bit_cast(bf16x8, operands[j * 64 + lane]);
+        b[j] = __builtin_bit_cast(bf16x8, operands[(4 + j) * 64 + lane]);
+    }
+    floatx4 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const unsigned long long r0 = __builtin_amdgcn_s_memrealtime(), c0 = __builtin_readcyclecounter();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j & 3], b[(j >> 1) & 3], acc[j], 0, 0, 0);
+    }
+    const unsigned long long c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) t += acc[j][0] + acc[j][1] + acc[j][2] + acc[j][3];
+    sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = t;
+    if (lane == 0) {
+        unsigned long long* st = stamps + 4 * (static_cast<size_t>(blockIdx.x) * (blockDim.x >> 6) + (threadIdx.x >> 6));
+        st[0] = r0;
+        st[1] = r1;
+        st[2] = c1 - c0;
+        st[3] = 1;
+    }
+}
+}  // namespace graft
+
+// operands: 8 x 64 x 16 bytes; sink: n_workgroups * threads floats; stamps: 4 values per wavefront
+// (real-time counter before and after the loop, core-clock cycles of the loop, 1).  threads is 256
+// (one wavefront per SIMD), 512, 768 or 1024 (four).  All device memory, all the caller's.
+extern "C" int32_t graft_mfma_calibration(const void* operands, float* sink, unsigned long long* stamps,
+                                          int32_t n_workgroups, int32_t threads, int32_t iters, void* stream) {
+    if (!operands || !sink || !stamps) return GRAFT_ERR_NULL;
+    if (n_workgroups < 1 || n_workgroups > (1 << 20) || (threads != 256 && threads != 512 && threads != 768 && threads != 1024) || iters < 1 || iters > (1 << 24))
+        return GRAFT_ERR_SHAPE;
+    hipLaunchKernelGGL(graft::mfma_calibration_kernel, dim3(n_workgroups), dim3(threads), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const graft::uintx4*>(operands), sink, iters, stamps);
+    return graft::check_launch();
+}
+
 // Timing build only (not part of the library's interface): device buffer that the MFMA kernel of
 // this host thread's following graft_tree_attn calls fills with AT_STAMPS 64-bit values per
 // workgroup; a call whose grid does not fit the buffer records nothing.  Null switches it off.

@@ -3,6 +3,7 @@
     python -m paper_2605_20104_amd.build --timing
     python -m paper_2605_20104_amd.timing --workload c3
     python -m paper_2605_20104_amd.timing --workload c3 --kv-heads 1 --splits 31 --row-tiles 1
+    python -m paper_2605_20104_amd.timing --mfma-calibration
 
 Runs graft_tree_attn of the timing build (libgraft_timing.so: the same kernel compiled with
 -DGRAFT_ATTN_STAMPS, which makes every workgroup record the 100 MHz real-time counter at the
@@ -11,6 +12,10 @@ inputs of a workload and prints, over all workgroups that ran the full number of
 each point was passed, the clock the stage loop ran at, and when the last workgroup ended.
 --kv-heads runs the same shape with fewer KV heads (fewer workgroups) and --splits /
 --row-tiles hold the launch plan, so that runs differ in the load on the chip only.
+--mfma-calibration instead runs a plain stream of independent v_mfma_f32_16x16x32_bf16 on every
+compute unit, with operands that are all zero, all one, or N(0,1) like the workloads' data, and
+prints the rate and the clock the chip holds under each: the ceiling the attention kernel's matrix
+work has on this machine, for its kind of data.
 Needs a GPU; the numbers of the product library are not affected (the stamps cost about
 0.3 us per workgroup).
 """
@@ -33,6 +38,50 @@ POINTS = ["lengths known", "table entries requested", "Q converted", "table and 
           "results written"]
 
 
+def mfma_calibration(lib):
+    lib.graft_mfma_calibration.restype = ctypes.c_int32
+    lib.graft_mfma_calibration.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32,
+                                           ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    gen = torch.Generator(device="cpu").manual_seed(20104)
+    kinds = {
+        "all zero": torch.zeros(8 * 64 * 8, dtype=torch.bfloat16),
+        "all one": torch.ones(8 * 64 * 8, dtype=torch.bfloat16),
+        "N(0,1)": torch.randn(8 * 64 * 8, generator=gen).to(torch.bfloat16),
+    }
+    stream = torch.cuda.current_stream().cuda_stream
+    print("plain stream of v_mfma_f32_16x16x32_bf16, eight independent accumulators per wavefront, %d compute units" % cus)
+    print("  operands   wavefronts/SIMD  workgroups   time (us)  by events   TFLOP/s   clock (GHz)  cycles per MFMA of a wavefront, its loop (us)")
+    for threads in (256, 512, 768, 1024):
+        for n_wg in (cus // 8, cus):
+            for name, host in kinds.items():
+                ops = host.cuda()
+                iters = 8000 * 256 // threads
+                sink = torch.empty(n_wg * threads, dtype=torch.float32, device="cuda")
+                n_waves = n_wg * (threads // 64)
+                stamps = torch.zeros(n_waves * 4, dtype=torch.int64, device="cuda")
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                for _ in range(3):                                   # the last launch is reported
+                    e0.record()
+                    rc = lib.graft_mfma_calibration(ops.data_ptr(), sink.data_ptr(), stamps.data_ptr(), n_wg, threads,
+                                                    iters, stream)
+                    e1.record()
+                    assert rc == 0, rc
+                torch.cuda.synchronize()
+                event_us = e0.elapsed_time(e1) * 1e3
+                if name == "all one":                                # every MFMA adds 32 to its 16 x 16 sums
+                    assert float(sink.min()) == float(sink.max()) == 1024.0 * iters, (float(sink.min()), iters)
+                st = stamps.cpu().numpy().view(np.uint64).reshape(n_waves, 4).astype(np.float64)
+                assert (st[:, 3] == 1).all()
+                span_us = (st[:, 1].max() - st[:, 0].min()) / 100.0      # first loop entered to last loop left
+                loop_us = (st[:, 1] - st[:, 0]) / 100.0
+                clk = (st[:, 2] / (loop_us * 1e3)).mean()                 # each wavefront's own loop
+                flops = float(n_waves) * iters * 8 * 16384.0
+                print("  %-10s %9d %13d %11.1f %10.1f %9.0f %11.3f %12.2f %10.1f"
+                      % (name, threads // 256, n_wg, span_us, event_us, flops / (span_us * 1e-6) / 1e12, clk,
+                         st[:, 2].mean() / (iters * 8), loop_us.mean()))
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
@@ -41,6 +90,7 @@ def main(argv=None):
     ap.add_argument("--row-tiles", type=int, default=0)
     ap.add_argument("--kv-buffers", type=int, default=0, help="K/V buffers the calls rotate over (default 4 for c3, else 1)")
     ap.add_argument("--calls", type=int, default=9, help="launches; the last one is reported")
+    ap.add_argument("--mfma-calibration", action="store_true", help="rate and clock of a plain MFMA stream instead")
     args = ap.parse_args(argv)
     if not torch.cuda.is_available():
         sys.exit("timing needs a GPU")
@@ -51,6 +101,8 @@ def main(argv=None):
 
     graft.LIB_PATH = graft_build.LIB_TIMING
     lib = graft.load_library()
+    if args.mfma_calibration:
+        return mfma_calibration(lib)
     lib.graft_attn_stamp_buffer.restype, lib.graft_attn_stamp_buffer.argtypes = ctypes.c_int32, [ctypes.c_void_p, ctypes.c_size_t]
     lib.graft_attn_force_plan.restype, lib.graft_attn_force_plan.argtypes = ctypes.c_int32, [ctypes.c_int32, ctypes.c_int32]
     n_stamps = lib.graft_attn_stamp_count()

@@ -36,17 +36,22 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_timing_build_is_the_same_interface_plus_its_own_calls(lib):
     """libgraft_timing.so (the attention kernel with time stamps) exports everything the header
-    declares and the three calls of the timing tool; the product library has none of those."""
+    declares and the calls of the timing tool; the product library has none of those."""
     from paper_2605_20104_amd import build
     if not os.path.exists(build.LIB_TIMING):
         pytest.skip("libgraft_timing.so is not built (python -m paper_2605_20104_amd.build --timing)")
     timing = ctypes.CDLL(build.LIB_TIMING)
     for n in declared_functions():
         assert getattr(timing, n) is not None
-    for n in ("graft_attn_stamp_buffer", "graft_attn_stamp_count", "graft_attn_force_plan"):
+    for n in ("graft_attn_stamp_buffer", "graft_attn_stamp_count", "graft_attn_force_plan", "graft_mfma_calibration"):
         assert getattr(timing, n) is not None
         assert not hasattr(lib, n), n
     assert timing.graft_attn_stamp_count() == 24
+    timing.graft_mfma_calibration.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int32] * 3 + [ctypes.c_void_p]
+    assert timing.graft_mfma_calibration(None, None, None, 1, 256, 1, None) == 1           # GRAFT_ERR_NULL
+    one = ctypes.c_void_p(8)                                                                # never dereferenced: the shape is refused first
+    assert timing.graft_mfma_calibration(one, one, one, 1, 300, 1, None) == 2              # GRAFT_ERR_SHAPE
+    assert timing.graft_mfma_calibration(one, one, one, 0, 256, 1, None) == 2
     # a held plan changes the workspace the same call asks for, and zeros give it back
     args = (1, 64, 40, 8, 128, 2052, 1)
     timing.graft_tree_attn_workspace_bytes.restype = ctypes.c_size_t
